@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the GR-KAN group-wise rational layer (FlashKAT hot path) on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic
+activations at the KAT-B shape (per-GPU batch 128, 197 tokens): the forward and
+the backward of both rational layers of a Transformer block,
+x1 [128,197,768] and x2 [128,197,3072], 8 groups, degrees (5,4), float32,
+in training order  fwd(x1) fwd(x2) bwd(x2) bwd(x1).
+`value` = elements that went through forward+backward per second, with the
+inputs resident in HBM.  Successive steps rotate over several buffer sets per layer so
+that no launch finds its inputs in the 256 MB last-level cache.
+
+Prints ONE JSON line (see the design doc for the field definitions).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
+# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); the
+# summaries are under profiles/.  None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="kat_b", choices=["kat_t", "kat_s", "kat_b"])
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--sets", type=int, default=0,
+                    help="buffer sets each layer rotates over (0 = enough that one rotation of the smallest "
+                         "kernel moves more than 1.1 GB, i.e. several times the 256 MB last-level cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detail", action="store_true", help="skip the per-kernel table")
+    return ap.parse_args()
+
+
+class Layer:
+    """Device buffers of one rational layer, `sets` copies of everything."""
+
+    def __init__(self, case, sets, torch, grkan):
+        import grkan_inputs
+
+        self.rows, self.D, self.G = case["rows"], case["D"], case["G"]
+        self.M = self.rows * self.D
+        self.es = 4 if case["dtype"] == "f32" else 2
+        if sets <= 0:
+            sets = max(2, -(-1_100_000_000 // self.fwd_bytes()))
+        self.sets = sets
+        first = grkan_inputs.upload(case, "cuda:0")
+        self.A, self.B = first["A"], first["B"]
+        self.x = [first["x"]] + [first["x"].clone() for _ in range(sets - 1)]
+        self.dy = [first["dy"]] + [first["dy"].clone() for _ in range(sets - 1)]
+        self.y = [torch.empty_like(first["x"]) for _ in range(sets)]
+        self.dx = [torch.empty_like(first["x"]) for _ in range(sets)]
+        self.dA = torch.empty_like(self.A)
+        self.dB = torch.empty_like(self.B)
+        io = grkan.GRKAN_F32 if case["dtype"] == "f32" else grkan.GRKAN_BF16
+        need = grkan.grkan_bwd_workspace_bytes(self.rows, self.D, self.G, io)
+        self.ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+        self.grkan = grkan
+
+    def fwd(self, i):
+        s = i % self.sets
+        self.grkan.grkan_fwd(self.x[s], self.A, self.B, out=self.y[s])
+
+    def bwd(self, i):
+        s = i % self.sets
+        self.grkan.grkan_bwd(self.x[s], self.dy[s], self.A, self.B, workspace=self.ws,
+                             out=(self.dx[s], self.dA, self.dB))
+
+    def fwd_bytes(self):
+        return 2 * self.es * self.M
+
+    def bwd_bytes(self):
+        return 3 * self.es * self.M
+
+
+def time_launches(torch, fn, n):
+    """Average device time (ms) of n launches of fn(i), from HIP events on the
+    launch stream."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for i in range(n):
+        ev[i][0].record()
+        fn(i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in ev)
+    return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+
+
+def cpu_baseline(cases):
+    """The fp64 oracle, as it stands, on the host cores: one forward+backward
+    pass over the same arrays."""
+    import numpy as np
+
+    from oracle import grkan_oracle
+
+    cores = len(os.sched_getaffinity(0))
+    threads = max(1, min(cores, grkan_oracle.max_threads()))
+    prepared = []
+    for c in cases:
+        prepared.append((c["x"].astype(np.float64), c["dy"].astype(np.float64),
+                         c["A"].astype(np.float64), c["B"].astype(np.float64)))
+    grkan_oracle.fwd(prepared[0][0][:64], prepared[0][2], prepared[0][3], threads=threads)  # load + warm
+    passes = 0
+    t0 = time.perf_counter()
+    while True:
+        for x, dy, A, B in prepared:
+            grkan_oracle.fwd(x, A, B, threads=threads)
+            grkan_oracle.bwd(x, dy, A, B, threads=threads)
+        passes += 1
+        dt = time.perf_counter() - t0
+        if dt * threads >= 15.0 or passes >= 20:  # about 15 core-seconds of oracle work
+            break
+    elems = passes * sum(int(p[0].size) for p in prepared)
+    return {
+        "value": elems / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+        "sample": "%d fwd+bwd pass(es) of the fp64 C oracle over the whole workload (%d elements in total, %.2f s wall)"
+                  % (passes, elems, dt),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path has no collective); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import grkan_inputs
+    import paper_2505_13813_amd as grkan
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    grkan.load_library()  # raises if the HIP library is not built: there is no fallback
+    torch.cuda.set_device(0)
+
+    cfg = grkan_inputs.CONFIGS[args.workload]
+    cases = [grkan_inputs.make_case(args.workload, t, dtype=args.dtype) for t, _ in cfg.tensors]
+    l1, l2 = (Layer(c, args.sets, torch, grkan) for c in cases)
+
+    def step(i):
+        l1.fwd(i)
+        l2.fwd(i)
+        l2.bwd(i)
+        l1.bwd(i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` steps; events bracket the dominant kernel
+    # (backward of x2) on the launch stream
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        l1.fwd(i)
+        l2.fwd(i)
+        ev[i][0].record()
+        l2.bwd(i)
+        ev[i][1].record()
+        l1.bwd(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = dt * 1e3 / args.steps
+    elems_per_step = l1.M + l2.M
+    bwd2_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    achieved = l2.bwd_bytes() / (bwd2_ms * 1e-3) / 1e9
+    key = "%s/%s/bwd_x2" % (args.workload, args.dtype)
+    roofline = {
+        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(key),
+        "kernel": "grkan_bwd on x2 [%d,%d] (stage 1 + stage 2), %d algorithmic bytes per launch, avg %.2f us"
+                  % (l2.rows, l2.D, l2.bwd_bytes(), bwd2_ms * 1e3),
+    }
+
+    detail = None
+    if not args.no_detail:
+        detail = {}
+        n = 40
+        for name, layer in (("x1", l1), ("x2", l2)):
+            for pname, fn, nbytes in (("fwd", layer.fwd, layer.fwd_bytes()), ("bwd", layer.bwd, layer.bwd_bytes())):
+                for _ in range(3):
+                    fn(0)
+                avg, med, mn = time_launches(torch, fn, n)
+                detail["%s_%s" % (pname, name)] = {
+                    "avg_us": avg * 1e3, "median_us": med * 1e3, "min_us": mn * 1e3,
+                    "GB/s": nbytes / (avg * 1e-3) / 1e9, "frac_of_peak": nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "Gelem/s": layer.M / (avg * 1e-3) / 1e9,
+                }
+
+    out = {
+        "metric": "GR-KAN fwd+bwd elements/s, KAT-%s shape" % args.workload[-1].upper(),
+        "value": elems_per_step / (dt / args.steps),
+        "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {
+            "workload": "%s: fwd+bwd of x1 [%d,197,%d] and x2 [%d,197,%d], G=%d, degrees (5,4)"
+                        % (args.workload, cfg.batch, l1.D, cfg.batch, l2.D, cfg.G),
+            "elements_per_step": elems_per_step, "buffer_sets": {"x1": l1.sets, "x2": l2.sets},
+            "hbm_GBs_whole_step": (l1.fwd_bytes() + l1.bwd_bytes() + l2.fwd_bytes() + l2.bwd_bytes()) / (dt / args.steps) / 1e9,
+        },
+        "roofline": roofline,
+    }
+    if detail is not None:
+        out["detail"] = detail
+    if not args.no_cpu_baseline:
+        del l1, l2
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(cases)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

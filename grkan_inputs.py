@@ -146,3 +146,20 @@ def make_case(config: str, tensor: Optional[str] = None, G: Optional[int] = None
     else:
         case.update(x=x, dy=dy)
     return case
+
+
+def upload(case: dict, device: str = "cuda:0") -> dict:
+    """Copy a case to the GPU as torch tensors (A, B float32; x, dy float32 or
+    bfloat16 from the stored bit patterns).  Data movement only."""
+    import torch
+
+    dev = {}
+    for k in ("A", "B"):
+        dev[k] = torch.from_numpy(np.ascontiguousarray(case[k])).to(device)
+    for k in ("x", "dy"):
+        if case["dtype"] == "bf16":
+            bits = np.ascontiguousarray(case[k + "_bits"]).view(np.int16)
+            dev[k] = torch.from_numpy(bits).to(device).view(torch.bfloat16)
+        else:
+            dev[k] = torch.from_numpy(np.ascontiguousarray(case[k])).to(device)
+    return dev

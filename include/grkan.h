@@ -1,0 +1,143 @@
+/*
+ * grkan.h - C ABI of the MI355X (gfx950) GR-KAN group-wise rational function.
+ *
+ * The operation is the safe Pade activation unit of the FlashKAT paper
+ * (Sec. "Kolmogorov-Arnold Transformer", Eq. "pade"), applied group-wise over
+ * channels, and its backward pass (Sec. "Gradient Computations", Eq. "grad_a",
+ * "grad_b", "grad_x", summed as in Eq. "accum" and "accum2"):
+ *
+ *     channel c of a row uses coefficient row g = c div d_g,  d_g = D / G
+ *     P(x)    = a_{g,0} + a_{g,1} x + ... + a_{g,5} x^5
+ *     Aden(x) = b_{g,1} x + ... + b_{g,4} x^4        (the paper writes A(x))
+ *     F(x)    = P(x) / (1 + |Aden(x)|)
+ *
+ * Common conventions of every entry point
+ *   - x, y, dy, dx: DEVICE pointers to contiguous row-major [rows, D] arrays of
+ *     the I/O dtype `io` (the paper's [B, N, d] tensor with B and N flattened).
+ *   - A: DEVICE pointer, float32 [G, 6], A[g*6 + i] = a_{g,i}, i = 0..5.
+ *     B: DEVICE pointer, float32 [G, 4], B[g*4 + (j-1)] = b_{g,j}, j = 1..4
+ *     (there is no b_0).  Coefficients and their gradients are float32 for
+ *     every I/O dtype; all arithmetic is float32.
+ *   - The caller owns every buffer.  The library never allocates, frees or
+ *     keeps device memory.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and return without synchronising.  The
+ *     status reports argument and launch errors only.
+ *   - Only (m, n) = (5, 4) is built; other degrees return GRKAN_ERR_DEGREE.
+ *   - D % G != 0 is GRKAN_ERR_SHAPE.  rows == 0 is valid.
+ *   - Pointers must be aligned to the element size.  16-byte aligned tensors
+ *     with d_g a multiple of 4 (float32) or 8 (bfloat16) take the fast
+ *     128-bit path; anything else silently takes a narrower-vector variant.
+ */
+#ifndef GRKAN_H_
+#define GRKAN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GRKAN_F32 = 0, /* x, y, dy, dx are float32 */
+    GRKAN_BF16 = 1 /* x, y, dy, dx are bfloat16; outputs rounded to nearest even */
+} grkan_dtype_t;
+
+typedef enum {
+    GRKAN_OK = 0,
+    GRKAN_ERR_NULL = 1,      /* a required pointer is NULL */
+    GRKAN_ERR_SHAPE = 2,     /* rows < 0, D <= 0, G <= 0 or D % G != 0 */
+    GRKAN_ERR_DEGREE = 3,    /* (m, n) != (5, 4) */
+    GRKAN_ERR_ALIGN = 4,     /* a pointer is not aligned to its element size */
+    GRKAN_ERR_WORKSPACE = 5, /* workspace missing or smaller than required */
+    GRKAN_ERR_DTYPE = 6,     /* unknown grkan_dtype_t */
+    GRKAN_ERR_LAUNCH = 7,    /* the HIP runtime rejected a launch or query */
+    GRKAN_ERR_UNSUPPORTED = 8 /* shape outside what the kernels index (see grkan_plan) */
+} grkan_status_t;
+
+/* Human-readable name of a status; never NULL; static storage. */
+const char *grkan_status_string(grkan_status_t status);
+
+/*
+ * Launch geometry the backward (and forward) pass uses for one shape.  Host
+ * logic only; exposed so that callers and tests can see how a shape is cut.
+ *
+ * One wavefront owns one group g and walks that group's [rows x d_g] slab in
+ * chunks of 64 vectors; `wg_per_bundle * waves_per_group_in_wg` wavefronts
+ * share a group.  A workgroup holds `groups_per_wg` adjacent groups (more than
+ * one only when a group's row segment is not a whole number of 128-byte lines).
+ */
+typedef struct {
+    int32_t vec;                  /* elements per lane per memory access */
+    int32_t vecs_per_segment;     /* d_g / vec */
+    int32_t waves_per_wg;         /* wavefronts in a workgroup */
+    int32_t groups_per_wg;        /* adjacent groups that share a workgroup */
+    int32_t waves_per_group_in_wg;/* waves_per_wg / groups_per_wg */
+    int32_t wg_per_bundle;        /* workgroups that share one bundle of groups */
+    int32_t grid;                 /* workgroups launched = (G / groups_per_wg) * wg_per_bundle */
+    int32_t fixed_col;            /* 1: every lane keeps its column for the whole kernel */
+    int64_t chunk_stride;         /* 64-vector chunks between two visits of one wavefront */
+    int32_t partials_per_group;   /* rows of 10 floats each group contributes to the workspace */
+} grkan_plan_t;
+
+/*
+ * Pure host function: the plan for a shape on a device with `num_cu` compute
+ * units that keeps `wg_per_cu` workgroups of this kernel resident per unit.
+ * `align_bytes` is the largest power of two (<= 16) that divides every tensor
+ * pointer.  Returns GRKAN_OK or the argument error.
+ */
+grkan_status_t grkan_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io,
+                          int32_t align_bytes, int32_t num_cu, int32_t wg_per_cu,
+                          grkan_plan_t *plan);
+
+/*
+ * Pure host function used by the tests: walks the plan exactly as the kernels
+ * do and checks that every vector of the [rows, D] array is visited exactly
+ * once and in bounds.  Returns 0 when the cover is exact, a positive count of
+ * offending vectors otherwise, -1 if the shape is too large to simulate
+ * (rows * D > 2^28).
+ */
+int64_t grkan_plan_cover_errors(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io,
+                                const grkan_plan_t *plan);
+
+/*
+ * Bytes of device workspace grkan_bwd needs for this shape on the current
+ * device (an upper bound over every alignment of the tensors).  Needs a HIP
+ * device; returns 0 on any error.
+ */
+size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io);
+
+/*
+ * Forward (Eq. "pade"):  y[r, c] = P_g(x[r, c]) / (1 + |Aden_g(x[r, c])|).
+ * y may alias x.
+ */
+grkan_status_t grkan_fwd(const void *x, const float *A, const float *B, void *y,
+                         int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
+                         grkan_dtype_t io, void *hip_stream);
+
+/*
+ * Backward (Eq. "grad_x", "grad_a", "grad_b", "accum", "accum2").  Nothing is
+ * saved from the forward pass; P, Aden and Q are recomputed from x.
+ *
+ *   dx[r, c]  = dy * ( P'/Q - s * Aden' * P / Q^2 ),   s = sign(Aden), s(0) = 0
+ *   dA[g, i]  = sum over all rows and the d_g channels of group g of  dy * x^i / Q
+ *   dB[g, j-1]= sum over the same elements of                       -dy * x^j * s * P / Q^2
+ *
+ * dA (float32 [G, 6]) and dB (float32 [G, 4]) are OVERWRITTEN with the sums.
+ * The sums use no atomic operations and a fixed order: for one build, device,
+ * shape and pointer alignment the results are bit-identical from run to run.
+ * dx may alias dy or x.  `workspace` is device scratch of at least
+ * grkan_bwd_workspace_bytes() bytes, 16-byte aligned, that must stay untouched
+ * until the enqueued work has finished; its contents afterwards are unspecified.
+ */
+grkan_status_t grkan_bwd(const void *x, const void *dy, const float *A, const float *B,
+                         void *dx, float *dA, float *dB,
+                         void *workspace, size_t workspace_bytes,
+                         int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
+                         grkan_dtype_t io, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRKAN_H_ */

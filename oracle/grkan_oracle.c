@@ -213,24 +213,47 @@ int grkan_oracle_bwd(const double *x, const double *dy, const double *A, const d
 
 /*
  * Condition scales for the error metric used by the parity tests (not part of
- * the method): the same expressions with every term replaced by its magnitude.
- *   Sy  = sum_i |a_i||x|^i / Q
- *   Sdx = |dy| * ( sum_i i|a_i||x|^(i-1) / Q + (sum_j j|b_j||x|^(j-1)) * (sum_i |a_i||x|^i) / Q^2 )
- *   RA[g][i] = sqrt( sum (dy x^i / Q)^2 ),  RB[g][j-1] = sqrt( sum (dy x^j s P / Q^2)^2 )
+ * the method).  A float32 evaluation of the paper's formulas rounds every
+ * monomial a_i x^i, b_j x^j (and i a_i x^(i-1), j b_j x^(j-1)) to relative
+ * precision eps; to first order the result then moves by at most eps times
+ *
+ *   Sy  = Pm/Q + |P| Am/Q^2
+ *   Sdx = |dy| ( dPm/Q + |Aden'| Pm/Q^2 + dAm |P|/Q^2 + Am (|P'|/Q^2 + 2 |Aden'| |P|/Q^3) )
+ *
+ * with the magnitude sums  Pm = sum |a_i||x|^i,  dPm = sum i|a_i||x|^(i-1),
+ * Am = sum |b_j||x|^j,  dAm = sum j|b_j||x|^(j-1).  The Am terms are the
+ * sensitivity of 1/Q and 1/Q^2 to cancellation inside Aden (large |x| next to
+ * a root of the denominator polynomial gives Q ~ 1 from terms of size >> 1).
+ * For the coefficient sums the same first-order scale of one term is
+ *
+ *   eA_i = |dy||x|^i/Q   (1 + Am/Q)
+ *   eB_j = |dy||x|^j |s| (Pm/Q^2 + 2 |P| Am/Q^3)
+ *
+ * and, the term errors being independent, the scale of a sum is the root of
+ * the sum of squares:  RA[g][i] = sqrt(sum eA_i^2), RB[g][j-1] = sqrt(sum eB_j^2).
+ * Where nothing cancels these reduce to |y|, |dx| and the root-sum-square of
+ * the terms, up to a factor below 4.
+ *
  * Any of the output pointers may be NULL.  dy may be NULL when only Sy is wanted.
+ * The root-sum-squares are plain (uncompensated) double sums: they only scale a tolerance.
  */
 int grkan_oracle_scales(const double *x, const double *dy, const double *A, const double *B,
                         double *Sy, double *Sdx, double *RA, double *RB,
-                        int64_t rows, int D, int G, int m, int n)
+                        int64_t rows, int D, int G, int m, int n, int threads)
 {
     int rc = check_args(rows, D, G, m, n);
     if (rc)
         return rc;
     const int dg = D / G;
     const int nc = m + 1 + n;
-    double *sq = (double *)calloc((size_t)G * nc, sizeof(double));
+    const int nsq = G * nc;
+    double *sq = (double *)calloc((size_t)nsq, sizeof(double));
     if (!sq)
         return 9;
+    threads = pick_threads(threads, rows);
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(threads) schedule(static) reduction(+ : sq[:nsq]) if (threads > 1)
+#endif
     for (int64_t r = 0; r < rows; ++r) {
         for (int c = 0; c < D; ++c) {
             const int g = c / dg;
@@ -238,7 +261,7 @@ int grkan_oracle_scales(const double *x, const double *dy, const double *A, cons
             const double *b = B + (size_t)g * n;
             const double xv = x[r * D + c];
             const double ax = fabs(xv);
-            const double d = dy ? dy[r * D + c] : 0.0;
+            const double d = dy ? fabs(dy[r * D + c]) : 0.0;
             elem_t e;
             eval_elem(xv, a, m, b, n, &e);
 
@@ -247,24 +270,28 @@ int grkan_oracle_scales(const double *x, const double *dy, const double *A, cons
             axp[0] = 1.0;
             for (int i = 1; i <= top; ++i)
                 axp[i] = axp[i - 1] * ax;
-            double Pm = 0.0, dPm = 0.0, dAm = 0.0;
+            double Pm = 0.0, dPm = 0.0, Am = 0.0, dAm = 0.0;
             for (int i = 0; i <= m; ++i)
                 Pm += fabs(a[i]) * axp[i];
             for (int i = 1; i <= m; ++i)
                 dPm += (double)i * fabs(a[i]) * axp[i - 1];
             for (int j = 1; j <= n; ++j)
+                Am += fabs(b[j - 1]) * axp[j];
+            for (int j = 1; j <= n; ++j)
                 dAm += (double)j * fabs(b[j - 1]) * axp[j - 1];
 
+            const double Q = e.Q, Q2 = Q * Q, Q3 = Q2 * Q;
+            const double aP = fabs(e.P), adP = fabs(e.dP), adA = fabs(e.dAden);
             if (Sy)
-                Sy[r * D + c] = Pm / e.Q;
+                Sy[r * D + c] = Pm / Q + aP * Am / Q2;
             if (Sdx)
-                Sdx[r * D + c] = fabs(d) * (dPm / e.Q + dAm * Pm / (e.Q * e.Q));
+                Sdx[r * D + c] = d * (dPm / Q + adA * Pm / Q2 + dAm * aP / Q2 + Am * (adP / Q2 + 2.0 * adA * aP / Q3));
             for (int i = 0; i <= m; ++i) {
-                double t = d * e.xp[i] / e.Q;
+                double t = d * axp[i] / Q * (1.0 + Am / Q);
                 sq[(size_t)g * nc + i] += t * t;
             }
             for (int j = 1; j <= n; ++j) {
-                double t = d * e.xp[j] * e.s * e.P / (e.Q * e.Q);
+                double t = d * axp[j] * fabs(e.s) * (Pm / Q2 + 2.0 * aP * Am / Q3);
                 sq[(size_t)g * nc + m + j] += t * t;
             }
         }

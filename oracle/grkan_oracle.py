@@ -48,7 +48,7 @@ def _load():
         lib.grkan_oracle_fwd.restype = i32
         lib.grkan_oracle_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, i64, i32, i32, i32, i32, i32]
         lib.grkan_oracle_bwd.restype = i32
-        lib.grkan_oracle_scales.argtypes = [dp, dp, dp, dp, dp, dp, dp, dp, i64, i32, i32, i32, i32]
+        lib.grkan_oracle_scales.argtypes = [dp, dp, dp, dp, dp, dp, dp, dp, i64, i32, i32, i32, i32, i32]
         lib.grkan_oracle_scales.restype = i32
         lib.grkan_oracle_max_threads.argtypes = []
         lib.grkan_oracle_max_threads.restype = i32
@@ -108,7 +108,7 @@ def bwd(x, dy, A, B, threads: int = 1):
     return dx, dA, dB
 
 
-def scales(x, dy, A, B):
+def scales(x, dy, A, B, threads: int = 1):
     """Condition scales (Sy, Sdx, RA, RB) used by the parity error metric."""
     x, A, B = _f64(x), _f64(A), _f64(B)
     dy = _f64(dy) if dy is not None else None
@@ -118,7 +118,7 @@ def scales(x, dy, A, B):
     RA = np.empty((G, m + 1), dtype=np.float64)
     RB = np.empty((G, n), dtype=np.float64)
     rc = _load().grkan_oracle_scales(_ptr(x), _ptr(dy), _ptr(A), _ptr(B), _ptr(Sy), _ptr(Sdx),
-                                     _ptr(RA), _ptr(RB), rows, D, G, m, n)
+                                     _ptr(RA), _ptr(RB), rows, D, G, m, n, threads)
     if rc:
         raise ValueError("grkan_oracle_scales failed with code %d" % rc)
     return Sy, Sdx, RA, RB

@@ -1,0 +1,20 @@
+"""MI355X-native GR-KAN group-wise rational function (FlashKAT hot path).
+
+The product is libgrkan.so (hand-written HIP for gfx950 behind the C ABI in
+include/grkan.h); this package is its thin Python binding.
+"""
+from .binding import (  # noqa: F401
+    GRKAN_BF16,
+    GRKAN_F32,
+    GrkanError,
+    Plan,
+    grkan_bwd,
+    grkan_bwd_raw,
+    grkan_bwd_workspace_bytes,
+    grkan_fwd,
+    grkan_fwd_raw,
+    load_library,
+    plan,
+    plan_cover_errors,
+    status_string,
+)

@@ -1,0 +1,186 @@
+"""Thin ctypes binding of libgrkan.so: argument marshalling only.
+
+Every step of the forward and backward pass runs in the HIP kernels behind the
+C ABI declared in include/grkan.h.  torch supplies device memory and the
+current stream; nothing here computes.  There is no CPU fallback: if the
+library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional, Tuple
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libgrkan.so"
+
+GRKAN_F32 = 0
+GRKAN_BF16 = 1
+M_DEGREE = 5
+N_DEGREE = 4
+
+_lib = None
+
+
+class GrkanError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [
+        ("vec", ctypes.c_int32),
+        ("vecs_per_segment", ctypes.c_int32),
+        ("waves_per_wg", ctypes.c_int32),
+        ("groups_per_wg", ctypes.c_int32),
+        ("waves_per_group_in_wg", ctypes.c_int32),
+        ("wg_per_bundle", ctypes.c_int32),
+        ("grid", ctypes.c_int32),
+        ("fixed_col", ctypes.c_int32),
+        ("chunk_stride", ctypes.c_int64),
+        ("partials_per_group", ctypes.c_int32),
+    ]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+def load_library():
+    """Load libgrkan.so (built in-tree by paper_2505_13813_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not LIB_PATH.exists():
+        raise RuntimeError(
+            "%s is missing: build it with `python -m paper_2505_13813_amd.build` "
+            "(there is no fallback path)" % LIB_PATH)
+    lib = ctypes.CDLL(str(LIB_PATH))
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    lib.grkan_status_string.argtypes = [ctypes.c_int]
+    lib.grkan_status_string.restype = ctypes.c_char_p
+    lib.grkan_plan.argtypes = [i64, i32, i32, ctypes.c_int, i32, i32, i32, ctypes.POINTER(Plan)]
+    lib.grkan_plan.restype = ctypes.c_int
+    lib.grkan_plan_cover_errors.argtypes = [i64, i32, i32, ctypes.c_int, ctypes.POINTER(Plan)]
+    lib.grkan_plan_cover_errors.restype = i64
+    lib.grkan_bwd_workspace_bytes.argtypes = [i64, i32, i32, ctypes.c_int]
+    lib.grkan_bwd_workspace_bytes.restype = sz
+    lib.grkan_fwd.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, ctypes.c_int, vp]
+    lib.grkan_fwd.restype = ctypes.c_int
+    lib.grkan_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i64, i32, i32, i32, i32, ctypes.c_int, vp]
+    lib.grkan_bwd.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().grkan_status_string(int(status)).decode()
+
+
+def plan(rows: int, D: int, G: int, io: int = GRKAN_F32, align_bytes: int = 16,
+         num_cu: int = 256, wg_per_cu: int = 4) -> Plan:
+    """Host-only: the launch geometry for a shape (see grkan_plan in grkan.h)."""
+    p = Plan()
+    st = load_library().grkan_plan(rows, D, G, io, align_bytes, num_cu, wg_per_cu, ctypes.byref(p))
+    if st:
+        raise GrkanError(st, "grkan_plan")
+    return p
+
+
+def plan_cover_errors(rows: int, D: int, G: int, io: int, p: Plan) -> int:
+    return int(load_library().grkan_plan_cover_errors(rows, D, G, io, ctypes.byref(p)))
+
+
+# ---------------------------------------------------------------- raw pointer level
+def grkan_bwd_workspace_bytes(rows: int, D: int, G: int, io: int) -> int:
+    return int(load_library().grkan_bwd_workspace_bytes(rows, D, G, io))
+
+
+def grkan_fwd_raw(x_ptr, A_ptr, B_ptr, y_ptr, rows, D, G, io, stream_ptr, m=M_DEGREE, n=N_DEGREE) -> int:
+    return int(load_library().grkan_fwd(x_ptr, A_ptr, B_ptr, y_ptr, rows, D, G, m, n, io, stream_ptr))
+
+
+def grkan_bwd_raw(x_ptr, dy_ptr, A_ptr, B_ptr, dx_ptr, dA_ptr, dB_ptr, ws_ptr, ws_bytes,
+                  rows, D, G, io, stream_ptr, m=M_DEGREE, n=N_DEGREE) -> int:
+    return int(load_library().grkan_bwd(x_ptr, dy_ptr, A_ptr, B_ptr, dx_ptr, dA_ptr, dB_ptr,
+                                        ws_ptr, ws_bytes, rows, D, G, m, n, io, stream_ptr))
+
+
+# ---------------------------------------------------------------- torch tensors
+def _io_of(t) -> int:
+    import torch
+
+    if t.dtype == torch.float32:
+        return GRKAN_F32
+    if t.dtype == torch.bfloat16:
+        return GRKAN_BF16
+    raise TypeError("x must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _check(x, A, B) -> Tuple[int, int, int]:
+    import torch
+
+    if not x.is_cuda or not A.is_cuda or not B.is_cuda:
+        raise ValueError("grkan runs on the GPU only: tensors must be on a HIP device")
+    if not x.is_contiguous() or not A.is_contiguous() or not B.is_contiguous():
+        raise ValueError("tensors must be contiguous")
+    if A.dtype != torch.float32 or B.dtype != torch.float32:
+        raise TypeError("A and B must be float32")
+    if A.dim() != 2 or B.dim() != 2 or A.shape[0] != B.shape[0]:
+        raise ValueError("A must be [G, m+1] and B [G, n]")
+    if x.dim() < 1:
+        raise ValueError("x needs at least one dimension")
+    D = int(x.shape[-1])
+    rows = int(x.numel() // D) if D else 0
+    return rows, D, int(A.shape[0])
+
+
+def _stream_ptr(stream=None):
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def grkan_fwd(x, A, B, out=None, stream=None):
+    """y = F(x) group-wise (FlashKAT paper, Eq. "pade").  Enqueues on the current stream."""
+    import torch
+
+    rows, D, G = _check(x, A, B)
+    y = torch.empty_like(x) if out is None else out
+    if y.shape != x.shape or y.dtype != x.dtype or not y.is_contiguous() or not y.is_cuda:
+        raise ValueError("out must match x")
+    st = grkan_fwd_raw(x.data_ptr(), A.data_ptr(), B.data_ptr(), y.data_ptr(), rows, D, G, _io_of(x),
+                       _stream_ptr(stream), int(A.shape[1]) - 1, int(B.shape[1]))
+    if st:
+        raise GrkanError(st, "grkan_fwd")
+    return y
+
+
+def grkan_bwd(x, dy, A, B, workspace: Optional["torch.Tensor"] = None, out=None, stream=None):
+    """(dx, dA, dB) of the group-wise rational function (Eq. "grad_x", "grad_a",
+    "grad_b", "accum", "accum2").  dA, dB are float32 and overwritten."""
+    import torch
+
+    rows, D, G = _check(x, A, B)
+    if dy.shape != x.shape or dy.dtype != x.dtype or not dy.is_contiguous() or not dy.is_cuda:
+        raise ValueError("dy must match x")
+    io = _io_of(x)
+    if out is None:
+        dx = torch.empty_like(x)
+        dA = torch.empty_like(A)
+        dB = torch.empty_like(B)
+    else:
+        dx, dA, dB = out
+    need = grkan_bwd_workspace_bytes(rows, D, G, io)
+    if need == 0:
+        raise GrkanError(7, "grkan_bwd_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    st = grkan_bwd_raw(x.data_ptr(), dy.data_ptr(), A.data_ptr(), B.data_ptr(), dx.data_ptr(),
+                       dA.data_ptr(), dB.data_ptr(), workspace.data_ptr(),
+                       workspace.numel() * workspace.element_size(), rows, D, G, io, _stream_ptr(stream),
+                       int(A.shape[1]) - 1, int(B.shape[1]))
+    if st:
+        raise GrkanError(st, "grkan_bwd")
+    return dx, dA, dB

@@ -1,0 +1,681 @@
+// GR-KAN group-wise rational function on gfx950 (MI355X): kernels and C ABI.
+//
+// The function and its gradients are those of the FlashKAT paper
+// (Eq. "pade"; Eq. "grad_a", "grad_b", "grad_x", summed as in Eq. "accum" and
+// "accum2").  The paper's own backward kernel (its Algorithm 2) accumulates the
+// coefficient gradients per thread block and then issues one atomic add per
+// block; here there are no atomics at all:
+//
+//   stage 1  one wavefront = one group.  Each lane streams 128-bit vectors of
+//            x and dy, writes dx, and keeps the ten partial sums in registers;
+//            the wavefront then folds them with DPP row/bank operations, the
+//            workgroup folds its wavefronts through LDS, and one row of ten
+//            floats per (workgroup, group) goes to a workspace.
+//   stage 2  one workgroup per group adds that group's workspace rows in a
+//            fixed order (in double) and overwrites dA / dB.
+//
+// Both orders are fixed by the launch geometry, which is a pure function of
+// shape, alignment and device, so dA / dB are bit-identical from run to run.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <mutex>
+
+#include "grkan_plan.h"
+
+namespace grkan {
+
+// --------------------------------------------------------------------------
+// coefficients (wave-uniform: they live in scalar registers)
+// --------------------------------------------------------------------------
+struct Coef {
+    float a0, a1, a2, a3, a4, a5;
+    float b1, b2, b3, b4;
+    float da2, da3, da4, da5; // i * a_i, the coefficients of P'
+    float db2, db3, db4;      // j * b_j, the coefficients of Aden'
+};
+
+__device__ __forceinline__ Coef load_coef(const float *__restrict__ A, const float *__restrict__ B, int g)
+{
+    const float *a = A + (size_t)g * 6;
+    const float *b = B + (size_t)g * 4;
+    Coef c;
+    c.a0 = a[0]; c.a1 = a[1]; c.a2 = a[2]; c.a3 = a[3]; c.a4 = a[4]; c.a5 = a[5];
+    c.b1 = b[0]; c.b2 = b[1]; c.b3 = b[2]; c.b4 = b[3];
+    c.da2 = 2.0f * c.a2; c.da3 = 3.0f * c.a3; c.da4 = 4.0f * c.a4; c.da5 = 5.0f * c.a5;
+    c.db2 = 2.0f * c.b2; c.db3 = 3.0f * c.b3; c.db4 = 4.0f * c.b4;
+    return c;
+}
+
+// --------------------------------------------------------------------------
+// per-element arithmetic (float32)
+// --------------------------------------------------------------------------
+
+// Eq. "pade": P by Horner, Aden = x * (b1 + b2 x + b3 x^2 + b4 x^3), and one
+// hardware reciprocal (1 ulp) instead of a division.
+__device__ __forceinline__ float fwd_elem(float x, const Coef &c)
+{
+    float p = fmaf(c.a5, x, c.a4);
+    p = fmaf(p, x, c.a3);
+    p = fmaf(p, x, c.a2);
+    p = fmaf(p, x, c.a1);
+    p = fmaf(p, x, c.a0);
+    float h = fmaf(c.b4, x, c.b3);
+    h = fmaf(h, x, c.b2);
+    h = fmaf(h, x, c.b1);
+    const float aden = h * x;
+    const float q = 1.0f + fabsf(aden);
+    return p * __builtin_amdgcn_rcpf(q);
+}
+
+// Eq. "grad_x", "grad_a", "grad_b" for one element; returns dx and adds this
+// element's ten terms to acc (acc[0..5] numerator, acc[6..9] denominator).
+// P/Q^2 is formed as (P r) r with r = 1/Q, so Q^2 is never computed.
+__device__ __forceinline__ float bwd_elem(float x, float d, const Coef &c, float (&acc)[kNumCoef])
+{
+    const float x2 = x * x;
+    const float x3 = x2 * x;
+    const float x4 = x2 * x2;
+    const float x5 = x4 * x;
+
+    float p = fmaf(c.a5, x, c.a4);
+    p = fmaf(p, x, c.a3);
+    p = fmaf(p, x, c.a2);
+    p = fmaf(p, x, c.a1);
+    p = fmaf(p, x, c.a0);
+
+    float dp = fmaf(c.da5, x, c.da4);
+    dp = fmaf(dp, x, c.da3);
+    dp = fmaf(dp, x, c.da2);
+    dp = fmaf(dp, x, c.a1);
+
+    float h = fmaf(c.b4, x, c.b3);
+    h = fmaf(h, x, c.b2);
+    h = fmaf(h, x, c.b1);
+    const float aden = h * x;
+
+    float dh = fmaf(c.db4, x, c.db3);
+    dh = fmaf(dh, x, c.db2);
+    dh = fmaf(dh, x, c.b1);
+
+    const float q = 1.0f + fabsf(aden);
+    const float r = __builtin_amdgcn_rcpf(q);
+
+    const float t = d * r; // dy / Q
+    acc[0] += t;
+    acc[1] = fmaf(t, x, acc[1]);
+    acc[2] = fmaf(t, x2, acc[2]);
+    acc[3] = fmaf(t, x3, acc[3]);
+    acc[4] = fmaf(t, x4, acc[4]);
+    acc[5] = fmaf(t, x5, acc[5]);
+
+    const float z0 = (p * r) * r;                                        // P / Q^2
+    const float z = aden > 0.0f ? z0 : (aden < 0.0f ? -z0 : 0.0f);       // sign(Aden) P / Q^2, sign(0) = 0
+    const float dx = d * fmaf(dp, r, -(dh * z));
+
+    const float wb = -(d * z);
+    acc[6] = fmaf(wb, x, acc[6]);
+    acc[7] = fmaf(wb, x2, acc[7]);
+    acc[8] = fmaf(wb, x3, acc[8]);
+    acc[9] = fmaf(wb, x4, acc[9]);
+    return dx;
+}
+
+// Global-memory (address space 1) byte pointers.  The loop-carried chunk base
+// is wave-uniform; passing its two halves through readfirstlane keeps it in
+// scalar registers, so that the memory instructions take the "scalar base +
+// 32-bit lane offset" form and the vector ALU does no address arithmetic in the
+// steady state.  The explicit address space keeps these global_* instructions
+// (a pointer rebuilt from integers would otherwise be treated as generic).
+typedef const __attribute__((address_space(1))) char *gcptr_t;
+typedef __attribute__((address_space(1))) char *gptr_t;
+
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t v)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// --------------------------------------------------------------------------
+// vector memory access: VEC elements of IO per lane, one instruction
+// --------------------------------------------------------------------------
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+struct bf16_t {
+    uint16_t bits;
+};
+
+template <int BYTES> struct RawOf;
+template <> struct RawOf<16> { using type = u32x4; };
+template <> struct RawOf<8> { using type = u32x2; };
+template <> struct RawOf<4> { using type = uint32_t; };
+template <> struct RawOf<2> { using type = uint16_t; };
+
+template <int BYTES> __device__ __forceinline__ uint32_t raw_word(const typename RawOf<BYTES>::type &r, int i)
+{
+    if constexpr (BYTES == 16 || BYTES == 8)
+        return r[i];
+    else
+        return (uint32_t)r;
+}
+
+template <typename IO, int VEC> __device__ __forceinline__ void load_vec(gcptr_t p, float (&out)[VEC])
+{
+    constexpr int BYTES = (int)sizeof(IO) * VEC;
+    using Raw = typename RawOf<BYTES>::type;
+    const Raw r = __builtin_nontemporal_load((const __attribute__((address_space(1))) Raw *)p);
+    if constexpr (sizeof(IO) == 4) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+            out[i] = __builtin_bit_cast(float, raw_word<BYTES>(r, i));
+    } else if constexpr (VEC == 1) {
+        out[0] = __builtin_bit_cast(float, (uint32_t)r << 16);
+    } else {
+        // bfloat16 -> float32 is a 16-bit shift; two elements per 32-bit word
+#pragma unroll
+        for (int i = 0; i < VEC / 2; ++i) {
+            const uint32_t w = raw_word<BYTES>(r, i);
+            out[2 * i] = __builtin_bit_cast(float, w << 16);
+            out[2 * i + 1] = __builtin_bit_cast(float, w & 0xffff0000u);
+        }
+    }
+}
+
+template <typename IO, int VEC> __device__ __forceinline__ void store_vec(gptr_t p, const float (&in)[VEC])
+{
+    constexpr int BYTES = (int)sizeof(IO) * VEC;
+    using Raw = typename RawOf<BYTES>::type;
+    Raw r;
+    if constexpr (sizeof(IO) == 4) {
+        if constexpr (VEC == 1) {
+            r = __builtin_bit_cast(uint32_t, in[0]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                r[i] = __builtin_bit_cast(uint32_t, in[i]);
+        }
+    } else if constexpr (VEC == 1) {
+        // round to nearest even
+        r = __builtin_bit_cast(uint16_t, static_cast<__bf16>(in[0]));
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC / 2; ++i) {
+            f32x2 f;
+            f[0] = in[2 * i];
+            f[1] = in[2 * i + 1];
+            const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+            if constexpr (VEC == 2)
+                r = w;
+            else
+                r[i] = w;
+        }
+    }
+    __builtin_nontemporal_store(r, (__attribute__((address_space(1))) Raw *)p);
+}
+
+// --------------------------------------------------------------------------
+// wavefront sum with DPP: quad swaps, half-row and row mirrors, then the two
+// row broadcasts; the total of all 64 lanes ends in lane 63.
+// --------------------------------------------------------------------------
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_get(float v)
+{
+    // lanes whose row is masked off receive 0
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false));
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_get<0xB1, 0xf>(v);  // quad_perm [1,0,3,2]
+    v += dpp_get<0x4E, 0xf>(v);  // quad_perm [2,3,0,1]
+    v += dpp_get<0x141, 0xf>(v); // row_half_mirror
+    v += dpp_get<0x140, 0xf>(v); // row_mirror: every lane of a row holds the row's sum
+    v += dpp_get<0x142, 0xa>(v); // row_bcast:15 into rows 1 and 3
+    v += dpp_get<0x143, 0xc>(v); // row_bcast:31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+// --------------------------------------------------------------------------
+// kernels
+// --------------------------------------------------------------------------
+struct FwdArgs {
+    const char *x;
+    char *y;
+    const float *A;
+    const float *B;
+    Walk walk;
+};
+
+struct BwdArgs {
+    const char *x;
+    const char *dy;
+    char *dx;
+    const float *A;
+    const float *B;
+    float *partial; // [G][wg_per_bundle][10]
+    Walk walk;
+};
+
+// Forward.  In fixed-column mode a wave holds one chunk in registers and
+// issues the load of its next chunk as soon as the current one is consumed,
+// before the store.  Deeper per-wave prefetch and more resident waves were
+// both measured slower: this memory system streams best with a few MB of loads
+// in flight chip-wide, and overlap comes from the other waves of the SIMD.
+template <typename IO, int VEC, bool FIXED>
+__global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs a)
+{
+    const Walk &p = a.walk;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
+    const Coef c = load_coef(a.A, a.B, id.g);
+    const int32_t n_it = full_visits(p, id.w);
+    const bool tail = owns_tail(p, id.w) && lane < p.rem;
+    constexpr int64_t ES = sizeof(IO);
+    const uint64_t x0 = reinterpret_cast<uint64_t>(a.x);
+    const uint64_t y0 = reinterpret_cast<uint64_t>(a.y);
+
+    auto one = [&](uint64_t off) {
+        float xv[VEC], yv[VEC];
+        load_vec<IO, VEC>((gcptr_t)(x0 + off), xv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            yv[e] = fwd_elem(xv[e], c);
+        store_vec<IO, VEC>((gptr_t)(y0 + off), yv);
+    };
+
+    if constexpr (FIXED) {
+        const uint64_t base0 = (uint64_t)(fixed_base0(p, id.g, id.w) * ES);
+        const uint64_t step = (uint64_t)(fixed_step(p) * ES);
+        const uint32_t lo = fixed_lane_offset(p, id.w, lane) * (uint32_t)ES;
+        // chunk `i` of this wave: scalar base + lane offset
+        auto xin = [&](int32_t i) { return (gcptr_t)uniform_u64(x0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
+        auto yout = [&](int32_t i) { return (gptr_t)uniform_u64(y0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
+
+        float xs[VEC];
+        if (n_it > 0)
+            load_vec<IO, VEC>(xin(0), xs);
+        for (int32_t it = 0; it < n_it; ++it) {
+            float yv[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+                yv[e] = fwd_elem(xs[e], c);
+            if (it + 1 < n_it)
+                load_vec<IO, VEC>(xin(it + 1), xs);
+            store_vec<IO, VEC>(yout(it), yv);
+        }
+        if (tail)
+            one(base0 + (uint64_t)(uint32_t)n_it * step + lo);
+    } else {
+        LanePos s = lane_start(p, id.w, lane);
+        for (int32_t it = 0; it < n_it; ++it) {
+            one((uint64_t)(elem_offset(p, id.g, s) * ES));
+            lane_advance(p, s);
+        }
+        if (tail)
+            one((uint64_t)(elem_offset(p, id.g, s) * ES));
+    }
+}
+
+// Backward, stage 1 (see the file header).
+template <typename IO, int VEC, bool FIXED>
+__global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const BwdArgs a)
+{
+    __shared__ float wave_part[kWavesPerWg][kNumCoef];
+
+    const Walk &p = a.walk;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
+    const Coef c = load_coef(a.A, a.B, id.g);
+    const int32_t n_it = full_visits(p, id.w);
+    const bool tail = owns_tail(p, id.w) && lane < p.rem;
+    constexpr int64_t ES = sizeof(IO);
+    const uint64_t x0 = reinterpret_cast<uint64_t>(a.x);
+    const uint64_t dy0 = reinterpret_cast<uint64_t>(a.dy);
+    const uint64_t dx0 = reinterpret_cast<uint64_t>(a.dx);
+
+    float acc[kNumCoef];
+#pragma unroll
+    for (int k = 0; k < kNumCoef; ++k)
+        acc[k] = 0.0f;
+
+    auto one = [&](uint64_t off) {
+        float xv[VEC], dv[VEC], ov[VEC];
+        load_vec<IO, VEC>((gcptr_t)(x0 + off), xv);
+        load_vec<IO, VEC>((gcptr_t)(dy0 + off), dv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            ov[e] = bwd_elem(xv[e], dv[e], c, acc);
+        store_vec<IO, VEC>((gptr_t)(dx0 + off), ov);
+    };
+
+    if constexpr (FIXED) {
+        const uint64_t base0 = (uint64_t)(fixed_base0(p, id.g, id.w) * ES);
+        const uint64_t step = (uint64_t)(fixed_step(p) * ES);
+        const uint32_t lo = fixed_lane_offset(p, id.w, lane) * (uint32_t)ES;
+        // chunk `i` of this wave: scalar base + lane offset
+        auto xin = [&](int32_t i) { return (gcptr_t)uniform_u64(x0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
+        auto dyin = [&](int32_t i) { return (gcptr_t)uniform_u64(dy0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
+        auto dxout = [&](int32_t i) { return (gptr_t)uniform_u64(dx0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
+
+        float xs[VEC], ds[VEC];
+        if (n_it > 0) {
+            load_vec<IO, VEC>(xin(0), xs);
+            load_vec<IO, VEC>(dyin(0), ds);
+        }
+        for (int32_t it = 0; it < n_it; ++it) {
+            float ov[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+                ov[e] = bwd_elem(xs[e], ds[e], c, acc);
+            if (it + 1 < n_it) {
+                load_vec<IO, VEC>(xin(it + 1), xs);
+                load_vec<IO, VEC>(dyin(it + 1), ds);
+            }
+            store_vec<IO, VEC>(dxout(it), ov);
+        }
+        if (tail)
+            one(base0 + (uint64_t)(uint32_t)n_it * step + lo);
+    } else {
+        LanePos s = lane_start(p, id.w, lane);
+        for (int32_t it = 0; it < n_it; ++it) {
+            one((uint64_t)(elem_offset(p, id.g, s) * ES));
+            lane_advance(p, s);
+        }
+        if (tail)
+            one((uint64_t)(elem_offset(p, id.g, s) * ES));
+    }
+
+    // registers -> wavefront (DPP) -> workgroup (LDS) -> one workspace row per group
+#pragma unroll
+    for (int k = 0; k < kNumCoef; ++k) {
+        const float s = wave_sum(acc[k]);
+        if (lane == 0)
+            wave_part[wv][k] = s;
+    }
+    __syncthreads();
+    const int tid = threadIdx.x;
+    if (tid < p.k * kNumCoef) {
+        const int gl = tid / kNumCoef;
+        const int kc = tid - gl * kNumCoef;
+        // waves gl, gl + k, gl + 2k, ... of this workgroup hold group (bundle * k + gl)
+        float s = 0.0f;
+        for (int sub = 0; sub < p.ns; ++sub)
+            s += wave_part[sub * p.k + gl][kc];
+        const int32_t bundle = (int32_t)blockIdx.x % p.nb;
+        const int32_t wgi = (int32_t)blockIdx.x / p.nb;
+        const int64_t g = (int64_t)bundle * p.k + gl;
+        a.partial[(g * p.wg_per_bundle + wgi) * kNumCoef + kc] = s;
+    }
+}
+
+// One workgroup per group: fixed-order sum of the group's workspace rows.
+constexpr int kStage2Threads = 256;
+
+__global__ __launch_bounds__(kStage2Threads) void grkan_bwd_stage2_kernel(const float *__restrict__ partial,
+                                                                          int32_t rows_per_group,
+                                                                          float *__restrict__ dA,
+                                                                          float *__restrict__ dB)
+{
+    __shared__ double red[kStage2Threads][kNumCoef];
+    const int g = blockIdx.x;
+    const int tid = threadIdx.x;
+    const float *base = partial + (size_t)g * rows_per_group * kNumCoef;
+
+    double s[kNumCoef];
+#pragma unroll
+    for (int k = 0; k < kNumCoef; ++k)
+        s[k] = 0.0;
+    for (int r = tid; r < rows_per_group; r += kStage2Threads) {
+#pragma unroll
+        for (int k = 0; k < kNumCoef; ++k)
+            s[k] += (double)base[(size_t)r * kNumCoef + k];
+    }
+#pragma unroll
+    for (int k = 0; k < kNumCoef; ++k)
+        red[tid][k] = s[k];
+    __syncthreads();
+    for (int half = kStage2Threads / 2; half > 0; half >>= 1) {
+        if (tid < half) {
+#pragma unroll
+            for (int k = 0; k < kNumCoef; ++k)
+                red[tid][k] += red[tid + half][k];
+        }
+        __syncthreads();
+    }
+    if (tid < 6)
+        dA[g * 6 + tid] = (float)red[0][tid];
+    else if (tid < kNumCoef)
+        dB[g * 4 + (tid - 6)] = (float)red[0][tid];
+}
+
+// --------------------------------------------------------------------------
+// host side
+// --------------------------------------------------------------------------
+struct DeviceInfo {
+    bool ready = false;
+    int num_cu = 0;
+};
+
+static std::mutex g_mu;
+static DeviceInfo g_dev[64];
+
+static bool device_info(int *dev_out, DeviceInfo *out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return false;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_dev[dev].ready) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            return false;
+        g_dev[dev].num_cu = n;
+        g_dev[dev].ready = true;
+    }
+    *dev_out = dev;
+    *out = g_dev[dev];
+    return true;
+}
+
+static int env_int(const char *name, int fallback)
+{
+    const char *s = std::getenv(name);
+    if (!s || !*s)
+        return fallback;
+    const int v = std::atoi(s);
+    return v > 0 ? v : fallback;
+}
+
+// Workgroups per compute unit the persistent grids are sized for (measured on
+// MI355X at the KAT shapes).  The float32 kernels are bound by HBM and stream
+// fastest with 3 workgroups (12 waves) per unit; the bfloat16 backward pass is
+// bound by the vector ALU and wants every wave slot.  The environment
+// variables override the defaults for experiments.
+static int fwd_wg_per_cu(grkan_dtype_t io) { return env_int("GRKAN_FWD_WG_PER_CU", io == GRKAN_F32 ? 3 : 4); }
+static int bwd_wg_per_cu(grkan_dtype_t io) { return env_int("GRKAN_BWD_WG_PER_CU", io == GRKAN_F32 ? 3 : 8); }
+
+static int32_t common_alignment(std::initializer_list<const void *> ptrs)
+{
+    uintptr_t bits = 16;
+    for (const void *q : ptrs)
+        bits |= reinterpret_cast<uintptr_t>(q);
+    return (int32_t)(bits & (~bits + 1)); // lowest set bit, at most 16
+}
+
+template <typename IO, int VEC> static hipError_t launch_fwd(const FwdArgs &a, bool fixed, int grid, hipStream_t st)
+{
+    if (fixed)
+        hipLaunchKernelGGL((grkan_fwd_kernel<IO, VEC, true>), dim3(grid), dim3(kThreadsPerWg), 0, st, a);
+    else
+        hipLaunchKernelGGL((grkan_fwd_kernel<IO, VEC, false>), dim3(grid), dim3(kThreadsPerWg), 0, st, a);
+    return hipGetLastError();
+}
+
+template <typename IO, int VEC> static hipError_t launch_bwd(const BwdArgs &a, bool fixed, int grid, hipStream_t st)
+{
+    if (fixed)
+        hipLaunchKernelGGL((grkan_bwd_stage1_kernel<IO, VEC, true>), dim3(grid), dim3(kThreadsPerWg), 0, st, a);
+    else
+        hipLaunchKernelGGL((grkan_bwd_stage1_kernel<IO, VEC, false>), dim3(grid), dim3(kThreadsPerWg), 0, st, a);
+    return hipGetLastError();
+}
+
+static hipError_t dispatch_fwd(grkan_dtype_t io, int vec, const FwdArgs &a, bool fixed, int grid, hipStream_t st)
+{
+    if (io == GRKAN_F32) {
+        switch (vec) {
+        case 4: return launch_fwd<float, 4>(a, fixed, grid, st);
+        case 2: return launch_fwd<float, 2>(a, fixed, grid, st);
+        case 1: return launch_fwd<float, 1>(a, fixed, grid, st);
+        }
+    } else {
+        switch (vec) {
+        case 8: return launch_fwd<bf16_t, 8>(a, fixed, grid, st);
+        case 4: return launch_fwd<bf16_t, 4>(a, fixed, grid, st);
+        case 2: return launch_fwd<bf16_t, 2>(a, fixed, grid, st);
+        case 1: return launch_fwd<bf16_t, 1>(a, fixed, grid, st);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+static hipError_t dispatch_bwd(grkan_dtype_t io, int vec, const BwdArgs &a, bool fixed, int grid, hipStream_t st)
+{
+    if (io == GRKAN_F32) {
+        switch (vec) {
+        case 4: return launch_bwd<float, 4>(a, fixed, grid, st);
+        case 2: return launch_bwd<float, 2>(a, fixed, grid, st);
+        case 1: return launch_bwd<float, 1>(a, fixed, grid, st);
+        }
+    } else {
+        switch (vec) {
+        case 8: return launch_bwd<bf16_t, 8>(a, fixed, grid, st);
+        case 4: return launch_bwd<bf16_t, 4>(a, fixed, grid, st);
+        case 2: return launch_bwd<bf16_t, 2>(a, fixed, grid, st);
+        case 1: return launch_bwd<bf16_t, 1>(a, fixed, grid, st);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+static grkan_status_t check_common(int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n, grkan_dtype_t io)
+{
+    if (m != 5 || n != 4)
+        return GRKAN_ERR_DEGREE;
+    return check_shape(rows, D, G, io);
+}
+
+static size_t workspace_for(const grkan_plan_t &pl, int32_t G)
+{
+    return (size_t)G * (size_t)pl.partials_per_group * kNumCoef * sizeof(float);
+}
+
+} // namespace grkan
+
+using namespace grkan;
+
+extern "C" size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io)
+{
+    if (check_shape(rows, D, G, io) != GRKAN_OK)
+        return 0;
+    int dev;
+    DeviceInfo info;
+    if (!device_info(&dev, &info))
+        return 0;
+    size_t need = 16; // never zero, so that callers can always allocate it
+    for (int align = elem_size(io); align <= 16; align *= 2) {
+        grkan_plan_t pl;
+        if (make_plan(rows, D, G, io, align, info.num_cu, bwd_wg_per_cu(io), &pl, nullptr) != GRKAN_OK)
+            return 0;
+        const size_t b = workspace_for(pl, G);
+        need = b > need ? b : need;
+    }
+    return need;
+}
+
+extern "C" grkan_status_t grkan_fwd(const void *x, const float *A, const float *B, void *y,
+                                    int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
+                                    grkan_dtype_t io, void *hip_stream)
+{
+    grkan_status_t st = check_common(rows, D, G, m, n, io);
+    if (st != GRKAN_OK)
+        return st;
+    if (!A || !B || (rows > 0 && (!x || !y)))
+        return GRKAN_ERR_NULL;
+    const int es = elem_size(io);
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) % es != 0 ||
+        (reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 4 != 0)
+        return GRKAN_ERR_ALIGN;
+    if (rows == 0)
+        return GRKAN_OK;
+
+    int dev;
+    DeviceInfo info;
+    if (!device_info(&dev, &info))
+        return GRKAN_ERR_LAUNCH;
+    grkan_plan_t pl;
+    FwdArgs a;
+    st = make_plan(rows, D, G, io, common_alignment({x, y}), info.num_cu, fwd_wg_per_cu(io), &pl, &a.walk);
+    if (st != GRKAN_OK)
+        return st;
+    a.x = static_cast<const char *>(x);
+    a.y = static_cast<char *>(y);
+    a.A = A;
+    a.B = B;
+    const hipError_t e = dispatch_fwd(io, pl.vec, a, pl.fixed_col != 0, pl.grid, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
+}
+
+extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *A, const float *B,
+                                    void *dx, float *dA, float *dB,
+                                    void *workspace, size_t workspace_bytes,
+                                    int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
+                                    grkan_dtype_t io, void *hip_stream)
+{
+    grkan_status_t st = check_common(rows, D, G, m, n, io);
+    if (st != GRKAN_OK)
+        return st;
+    if (!A || !B || !dA || !dB || (rows > 0 && (!x || !dy || !dx)))
+        return GRKAN_ERR_NULL;
+    const int es = elem_size(io);
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(dx)) % es != 0 ||
+        (reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(dA) |
+         reinterpret_cast<uintptr_t>(dB)) % 4 != 0)
+        return GRKAN_ERR_ALIGN;
+
+    int dev;
+    DeviceInfo info;
+    if (!device_info(&dev, &info))
+        return GRKAN_ERR_LAUNCH;
+    grkan_plan_t pl;
+    BwdArgs a;
+    st = make_plan(rows, D, G, io, common_alignment({x, dy, dx}), info.num_cu, bwd_wg_per_cu(io), &pl, &a.walk);
+    if (st != GRKAN_OK)
+        return st;
+    const size_t need = workspace_for(pl, G);
+    if (need > 0 && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0))
+        return GRKAN_ERR_WORKSPACE;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    a.x = static_cast<const char *>(x);
+    a.dy = static_cast<const char *>(dy);
+    a.dx = static_cast<char *>(dx);
+    a.A = A;
+    a.B = B;
+    a.partial = static_cast<float *>(workspace);
+    if (pl.grid > 0) {
+        const hipError_t e = dispatch_bwd(io, pl.vec, a, pl.fixed_col != 0, pl.grid, stream);
+        if (e != hipSuccess)
+            return GRKAN_ERR_LAUNCH;
+    }
+    // with no rows there are no workspace rows and stage 2 writes zeros
+    hipLaunchKernelGGL(grkan_bwd_stage2_kernel, dim3(G), dim3(kStage2Threads), 0, stream, a.partial,
+                       pl.partials_per_group, dA, dB);
+    return hipGetLastError() == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
+}

@@ -1,0 +1,258 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 oracle, element
+by element, on the seeded synthetic inputs."""
+import numpy as np
+import pytest
+
+import grkan_inputs
+from parity_util import TOL, assert_parity, errors, run_gpu, run_oracle, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def custom_case(seed, rows, D, G, dtype="f32", x_scale=1.0):
+    rng = np.random.default_rng(seed)
+    A = (rng.uniform(-1, 1, size=(G, 6)) / (np.arange(6) + 1.0)).astype(np.float32)
+    B = rng.uniform(-0.5, 0.5, size=(G, 4)).astype(np.float32)
+    x = (rng.standard_normal((rows, D)) * x_scale).astype(np.float32)
+    dy = rng.standard_normal((rows, D)).astype(np.float32)
+    case = dict(dtype=dtype, rows=rows, D=D, G=G, A=A, B=B, x=x, dy=dy)
+    if dtype == "bf16":
+        for k in ("x", "dy"):
+            bits = grkan_inputs.round_to_bf16_bits(case[k])
+            case[k + "_bits"] = bits
+            case[k] = grkan_inputs.bf16_bits_to_f32(bits)
+    return case
+
+
+@pytest.fixture(scope="module")
+def threads(oracle):
+    return max(1, min(16, oracle.max_threads()))
+
+
+# ------------------------------------------------------------------ config 0
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_config_elementwise(oracle, dtype):
+    case = grkan_inputs.make_case("tiny", dtype=dtype)
+    gpu = run_gpu(case)
+    ref = run_oracle(oracle, case)
+    err = assert_parity(gpu, ref, dtype, label="tiny/" + dtype)
+    print("tiny", dtype, err)
+
+
+# ------------------------------------------------------------------ shapes that span tiles, tails, vector widths
+SHAPES = [
+    # rows, D, G            what it exercises
+    (1000, 192, 8),       # KAT-T x1 segment (96 B): 4 groups per workgroup, ragged tail
+    (999, 768, 8),        # KAT-T x2 / KAT-B x1 segment, odd row count
+    (513, 384, 8),        # KAT-S x1: 2 groups per workgroup
+    (257, 1536, 8),       # KAT-S x2
+    (301, 3072, 8),       # KAT-B x2 segment
+    (129, 3072, 1),       # one group
+    (131, 3072, 64),      # 64 groups
+    (37, 40, 5),          # d_g = 8
+    (33, 30, 5),          # d_g = 6  -> 2-wide vectors (fp32)
+    (29, 35, 5),          # d_g = 7  -> scalar path
+    (1, 192, 8), (2, 8, 8), (5, 7, 1), (64, 64, 1), (1, 1, 1),
+    (3, 64 * 4 * 1009, 64),  # general (non fixed-column) walk
+]
+
+
+@pytest.mark.parametrize("rows,D,G", SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_shapes_elementwise(oracle, rows, D, G, dtype):
+    case = custom_case(rows * 7919 + D * 31 + G, rows, D, G, dtype)
+    gpu = run_gpu(case)
+    ref = run_oracle(oracle, case, threads=4)
+    assert_parity(gpu, ref, dtype, label="%dx%d G=%d %s" % (rows, D, G, dtype))
+
+
+@pytest.mark.parametrize("dtype,offset", [("f32", 1), ("f32", 2), ("bf16", 1), ("bf16", 2), ("bf16", 4)])
+def test_misaligned_tensors_take_a_narrower_path(oracle, dtype, offset):
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    rows, D, G = 61, 192, 8
+    case = custom_case(4242 + offset, rows, D, G, dtype)
+    dev = to_device(case)
+    n = rows * D
+
+    def shifted(t):
+        buf = torch.empty(n + 16, dtype=t.dtype, device=t.device)
+        view = buf[offset:offset + n].view(rows, D)
+        view.copy_(t)
+        return view
+
+    x, dy = shifted(dev["x"]), shifted(dev["dy"])
+    y = shifted(torch.zeros_like(dev["x"]))
+    dx = shifted(torch.zeros_like(dev["x"]))
+    dA, dB = torch.empty_like(dev["A"]), torch.empty_like(dev["B"])
+    grkan.grkan_fwd(x, dev["A"], dev["B"], out=y)
+    grkan.grkan_bwd(x, dy, dev["A"], dev["B"], out=(dx, dA, dB))
+    torch.cuda.synchronize()
+    gpu = dict(y=to_host(y), dx=to_host(dx), dA=to_host(dA), dB=to_host(dB))
+    ref = run_oracle(oracle, case)
+    assert_parity(gpu, ref, dtype, label="misaligned %s +%d" % (dtype, offset))
+
+
+# ------------------------------------------------------------------ degenerate cases of the method
+def test_identity_init_is_exact(oracle):
+    # A = e_1, B = 0 (the paper's first-layer init): y = x, dx = dy, dB = 0 exactly
+    case = custom_case(5, 300, 192, 8)
+    case["A"] = np.zeros((8, 6), np.float32)
+    case["A"][:, 1] = 1.0
+    case["B"] = np.zeros((8, 4), np.float32)
+    gpu = run_gpu(case)
+    assert np.array_equal(gpu["y"], case["x"].astype(np.float64))
+    assert np.array_equal(gpu["dx"], case["dy"].astype(np.float64))
+    assert np.array_equal(gpu["dB"], np.zeros((8, 4)))
+    ref = run_oracle(oracle, case)
+    assert_parity(gpu, ref, "f32", label="identity")
+
+
+def test_sign_of_zero_denominator_polynomial_is_zero(oracle):
+    # x = 0 everywhere: Aden = 0, so dx = dy * a_1 and the b-gradients vanish
+    case = custom_case(6, 64, 48, 4)
+    case["x"][:] = 0.0
+    case["x"][::3, ::5] = 0.5
+    gpu = run_gpu(case)
+    ref = run_oracle(oracle, case)
+    assert_parity(gpu, ref, "f32", label="zeros")
+    zero = case["x"] == 0.0
+    a1 = np.repeat(case["A"][:, 1].astype(np.float64), 12)[None, :]
+    want = (case["dy"].astype(np.float64) * a1)[zero]
+    np.testing.assert_allclose(gpu["dx"][zero], want, rtol=1e-6)
+
+
+def test_large_inputs_stay_finite(oracle):
+    case = custom_case(7, 128, 384, 8, x_scale=300.0)
+    gpu = run_gpu(case)
+    ref = run_oracle(oracle, case)
+    assert_parity(gpu, ref, "f32", label="large |x|")
+
+
+def test_empty_input():
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    x = torch.empty(0, 192, device="cuda:0")
+    A = torch.ones(8, 6, device="cuda:0")
+    B = torch.ones(8, 4, device="cuda:0")
+    y = grkan.grkan_fwd(x, A, B)
+    dx, dA, dB = grkan.grkan_bwd(x, x, A, B)
+    torch.cuda.synchronize()
+    assert y.shape == (0, 192) and dx.shape == (0, 192)
+    assert torch.count_nonzero(dA).item() == 0 and torch.count_nonzero(dB).item() == 0
+
+
+def test_outputs_may_alias_inputs(oracle):
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    case = custom_case(8, 200, 768, 8)
+    dev = to_device(case)
+    ref = run_oracle(oracle, case, threads=4)
+    xa = dev["x"].clone()
+    grkan.grkan_fwd(xa, dev["A"], dev["B"], out=xa)            # y over x
+    dya = dev["dy"].clone()
+    dA, dB = torch.empty_like(dev["A"]), torch.empty_like(dev["B"])
+    grkan.grkan_bwd(dev["x"], dya, dev["A"], dev["B"], out=(dya, dA, dB))  # dx over dy
+    torch.cuda.synchronize()
+    gpu = dict(y=to_host(xa), dx=to_host(dya), dA=to_host(dA), dB=to_host(dB))
+    assert_parity(gpu, ref, "f32", label="aliased")
+
+
+def test_errors_from_the_device_side_checks():
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    x = torch.zeros(4, 192, device="cuda:0")
+    A = torch.zeros(8, 6, device="cuda:0")
+    B = torch.zeros(8, 4, device="cuda:0")
+    small = torch.empty(8, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(grkan.GrkanError) as e:
+        grkan.grkan_bwd(x, x, A, B, workspace=small)
+    assert e.value.status == 5
+    with pytest.raises(grkan.GrkanError) as e:
+        grkan.grkan_fwd(x, torch.zeros(8, 5, device="cuda:0"), B)
+    assert e.value.status == 3
+    with pytest.raises(grkan.GrkanError) as e:
+        grkan.grkan_fwd(x, torch.zeros(7, 6, device="cuda:0"), torch.zeros(7, 4, device="cuda:0"))
+    assert e.value.status == 2
+
+
+# ------------------------------------------------------------------ determinism
+@pytest.mark.parametrize("config,tensor,dtype", [("tiny", "x", "f32"), ("kat_b", "x2", "f32"), ("kat_b", "x1", "bf16")])
+def test_coefficient_gradients_are_bit_identical_run_to_run(config, tensor, dtype):
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    case = grkan_inputs.make_case(config, tensor, dtype=dtype)
+    dev = to_device(case)
+    runs = []
+    for _ in range(4):
+        dx, dA, dB = grkan.grkan_bwd(dev["x"], dev["dy"], dev["A"], dev["B"])
+        torch.cuda.synchronize()
+        runs.append((dA.cpu().numpy().copy(), dB.cpu().numpy().copy(), dx.view(torch.int16 if dtype == "bf16" else torch.int32).cpu().numpy().copy()))
+    for dA, dB, dx in runs[1:]:
+        assert np.array_equal(dA.view(np.uint32), runs[0][0].view(np.uint32))
+        assert np.array_equal(dB.view(np.uint32), runs[0][1].view(np.uint32))
+        assert np.array_equal(dx, runs[0][2])
+
+
+# ------------------------------------------------------------------ full-size configurations
+FULL = [
+    ("kat_t", "x1", "f32", 8), ("kat_t", "x2", "f32", 8),
+    ("kat_s", "x1", "f32", 8), ("kat_s", "x2", "f32", 8),
+    ("kat_b", "x1", "f32", 8), ("kat_b", "x2", "f32", 8),
+    ("kat_b", "x1", "bf16", 8), ("kat_b", "x2", "bf16", 8),
+    ("stress", "x", "f32", 1), ("stress", "x", "f32", 8), ("stress", "x", "f32", 64),
+]
+
+_case_cache = {}
+
+
+def full_case(config, tensor, dtype, G):
+    key = (config, tensor, dtype)
+    if key not in _case_cache:
+        _case_cache.clear()
+        _case_cache[key] = grkan_inputs.make_case(config, tensor, dtype=dtype)
+    case = dict(_case_cache[key])
+    cfg = grkan_inputs.CONFIGS[config]
+    case["A"], case["B"] = grkan_inputs.coefficients(cfg, G)
+    case["G"] = G
+    return case
+
+
+@pytest.mark.parametrize("config,tensor,dtype,G", FULL)
+def test_full_size_configuration(oracle, threads, config, tensor, dtype, G):
+    """At the bench's sizes and launch configuration: dA / dB against the oracle
+    over the whole array, y / dx on sampled rows (first, last, and random)."""
+    case = full_case(config, tensor, dtype, G)
+    gpu = run_gpu(case)
+    rows = case["rows"]
+    rng = np.random.default_rng(99)
+    pick = np.unique(np.concatenate([np.arange(0, 8), np.arange(rows - 8, rows), rng.integers(0, rows, 240)]))
+    ref_s = run_oracle(oracle, case, threads=threads, rows=pick)
+    err = errors(gpu, dict(y=ref_s["y"], dx=ref_s["dx"], Sy=ref_s["Sy"], Sdx=ref_s["Sdx"]), rows=pick)
+    assert err["y"] <= TOL[dtype]["y"], err
+    assert err["dx"] <= TOL[dtype]["dx"], err
+
+    x = case["x"].astype(np.float64)
+    dy = case["dy"].astype(np.float64)
+    A, B = case["A"].astype(np.float64), case["B"].astype(np.float64)
+    _, dA, dB = oracle.bwd(x, dy, A, B, threads=threads)
+    _, _, RA, RB = oracle.scales(x, dy, A, B, threads=threads)
+    eA = float(np.max(np.abs(gpu["dA"] - dA) / np.maximum(np.abs(dA), RA)))
+    eB = float(np.max(np.abs(gpu["dB"] - dB) / np.maximum(np.abs(dB), RB)))
+    print(config, tensor, dtype, "G=%d" % G, "y %.2e dx %.2e dA %.2e dB %.2e" % (err["y"], err["dx"], eA, eB))
+    assert np.all(np.isfinite(gpu["dA"])) and np.all(np.isfinite(gpu["dB"]))
+    assert eA <= TOL[dtype]["dA"] and eB <= TOL[dtype]["dB"], (eA, eB)
+    # plain relative error where the sums are well conditioned
+    well = np.abs(dA) > 10 * RA
+    if well.any():
+        assert np.max(np.abs(gpu["dA"] - dA)[well] / np.abs(dA)[well]) <= TOL[dtype]["dA"]

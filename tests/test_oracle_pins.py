@@ -344,3 +344,50 @@ def test_scales_bound_the_values(oracle):
     n_terms = 10 * 4
     assert np.all(np.abs(dA) <= RA * np.sqrt(n_terms) * (1 + 1e-12))
     assert np.all(np.abs(dB) <= RB * np.sqrt(n_terms) * (1 + 1e-12))
+
+
+def test_scales_bound_a_float32_evaluation(oracle):
+    """The condition scales must cover what float32 rounding does to the
+    formulas (otherwise the parity tolerance would be unreachable for any
+    float32 kernel) without being orders of magnitude loose: a straightforward
+    float32 numpy evaluation on heavy-tailed inputs stays within ~16 eps of
+    them, and exceeds 1e-3 eps of them somewhere."""
+    rng = np.random.default_rng(13)
+    rows, D, G = 4000, 32, 4
+    A = (rng.uniform(-1, 1, size=(G, 6)) / (np.arange(6) + 1.0)).astype(np.float32)
+    B = rng.uniform(-0.5, 0.5, size=(G, 4)).astype(np.float32)
+    x = rng.standard_t(3, size=(rows, D)).astype(np.float32)
+    dy = rng.standard_normal((rows, D)).astype(np.float32)
+    f = np.float32
+    xg = x.reshape(rows, G, D // G)
+    a = A[None, :, :, None]
+    b = B[None, :, :, None]
+    P = a[:, :, 5]
+    for i in (4, 3, 2, 1, 0):
+        P = (P * xg + a[:, :, i]).astype(f)
+    dP = (f(5) * a[:, :, 5])
+    for i in (4, 3, 2, 1):
+        dP = (dP * xg + f(i) * a[:, :, i]).astype(f)
+    h = b[:, :, 3]
+    for j in (2, 1, 0):
+        h = (h * xg + b[:, :, j]).astype(f)
+    aden = (h * xg).astype(f)
+    dh = f(4) * b[:, :, 3]
+    for j in (2, 1, 0):
+        dh = (dh * xg + f(j + 1) * b[:, :, j]).astype(f)
+    q = (f(1) + np.abs(aden)).astype(f)
+    y32 = (P / q).astype(f)
+    dx32 = (dy.reshape(xg.shape) * (dP / q - np.sign(aden) * dh * P / q / q)).astype(f)
+
+    x64, dy64, A64, B64 = (v.astype(np.float64) for v in (x, dy, A, B))
+    y = oracle.fwd(x64, A64, B64)
+    dx, _, _ = oracle.bwd(x64, dy64, A64, B64)
+    Sy, Sdx, _, _ = oracle.scales(x64, dy64, A64, B64)
+    eps = 2.0 ** -24
+    ry = np.abs(y32.reshape(rows, D) - y) / np.maximum(np.abs(y), Sy)
+    rdx = np.abs(dx32.reshape(rows, D) - dx) / np.maximum(np.abs(dx), Sdx)
+    assert ry.max() <= 16 * eps and rdx.max() <= 16 * eps, (ry.max() / eps, rdx.max() / eps)
+    assert ry.max() >= 1e-3 * eps and rdx.max() >= 1e-3 * eps
+    # and the plain relative error really is unbounded by such a constant on these inputs
+    plain = np.abs(dx32.reshape(rows, D) - dx) / np.abs(dx)
+    assert plain.max() > 16 * eps

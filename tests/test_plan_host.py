@@ -1,0 +1,85 @@
+"""Host logic of the GPU library: launch planning and the exact-cover check of
+the kernels' index walk.  Runs without a GPU (no compute call is made)."""
+import itertools
+
+import pytest
+
+import paper_2505_13813_amd as grkan
+from paper_2505_13813_amd import GRKAN_BF16, GRKAN_F32
+
+# (rows, D, G) of every configuration the bench and parity tests use, cut to a
+# size the simulator walks in well under a second, plus awkward shapes
+SHAPES = [
+    (788, 192, 8),      # tiny config: 96-byte segments -> 4 groups per workgroup
+    (1000, 768, 8),     # KAT-T x2 / KAT-B x1
+    (300, 384, 8), (300, 1536, 8), (301, 3072, 8),
+    (130, 3072, 1), (130, 3072, 64),
+    (37, 40, 5), (33, 30, 5), (29, 35, 5), (1, 192, 8), (3, 8, 8), (5, 7, 1), (64, 64, 1),
+    (1023, 24, 3), (2, 6 * 1009, 6),
+]
+
+
+@pytest.mark.parametrize("rows,D,G", SHAPES)
+@pytest.mark.parametrize("io", [GRKAN_F32, GRKAN_BF16])
+def test_walk_covers_every_vector_exactly_once(rows, D, G, io):
+    es = 4 if io == GRKAN_F32 else 2
+    for align, (num_cu, wg_per_cu) in itertools.product((16, 8, es), ((256, 4), (256, 8), (3, 1))):
+        p = grkan.plan(rows, D, G, io, align_bytes=align, num_cu=num_cu, wg_per_cu=wg_per_cu)
+        assert p.grid == (G // p.groups_per_wg) * p.wg_per_bundle
+        assert p.vec * es <= align and (D // G) % p.vec == 0
+        assert grkan.plan_cover_errors(rows, D, G, io, p) == 0, p.as_dict()
+
+
+def test_general_walk_is_used_when_columns_cannot_be_fixed_and_still_covers():
+    # d_g = 4 * 1009: 64 * (waves per group) is never a multiple of 1009 within the grid budget
+    rows, G, dg = 3, 64, 4 * 1009
+    p = grkan.plan(rows, G * dg, G, GRKAN_F32)
+    assert p.fixed_col == 0
+    assert grkan.plan_cover_errors(rows, G * dg, G, GRKAN_F32, p) == 0
+
+
+def test_headline_plans():
+    # KAT-B x2 fp32: 1536-byte segments are line aligned -> one group per
+    # workgroup, all four waves share it, fixed columns, one persistent wave of
+    # workgroups
+    p = grkan.plan(25216, 3072, 8, GRKAN_F32)
+    assert (p.vec, p.groups_per_wg, p.waves_per_group_in_wg, p.fixed_col) == (4, 1, 4, 1)
+    assert p.grid <= 256 * 4 and p.grid >= 256 * 4 * 0.95
+    assert (64 * p.chunk_stride) % p.vecs_per_segment == 0
+    # KAT-B x1 bf16: 192-byte segments -> two adjacent groups per workgroup
+    p = grkan.plan(25216, 768, 8, GRKAN_BF16)
+    assert (p.vec, p.groups_per_wg, p.fixed_col) == (8, 2, 1)
+    # stress, one group
+    p = grkan.plan(50432, 3072, 1, GRKAN_F32)
+    assert p.groups_per_wg == 1 and p.fixed_col == 1
+
+
+def test_plan_is_deterministic():
+    a = grkan.plan(25216, 3072, 8, GRKAN_F32).as_dict()
+    b = grkan.plan(25216, 3072, 8, GRKAN_F32).as_dict()
+    assert a == b
+
+
+def test_empty_input_plans_no_work():
+    p = grkan.plan(0, 192, 8, GRKAN_F32)
+    assert p.grid == 0 and p.partials_per_group == 0
+    assert grkan.plan_cover_errors(0, 192, 8, GRKAN_F32, p) == 0
+
+
+@pytest.mark.parametrize("rows,D,G,io,status", [
+    (-1, 192, 8, GRKAN_F32, 2), (4, 0, 8, GRKAN_F32, 2), (4, 192, 0, GRKAN_F32, 2),
+    (4, 190, 8, GRKAN_F32, 2), (4, 192, 8, 7, 6),
+])
+def test_plan_rejects_bad_arguments(rows, D, G, io, status):
+    with pytest.raises(grkan.GrkanError) as e:
+        grkan.plan(rows, D, G, io)
+    assert e.value.status == status
+
+
+def test_a_corrupted_plan_fails_the_cover_check():
+    p = grkan.plan(100, 192, 8, GRKAN_F32)
+    p.wg_per_bundle -= 3  # fewer waves but the same stride bookkeeping: still a cover
+    assert grkan.plan_cover_errors(100, 192, 8, GRKAN_F32, p) == 0
+    p.fixed_col = 1
+    p.wg_per_bundle += 1  # 64 * waves is no longer a multiple of the segment length
+    assert grkan.plan_cover_errors(100, 192, 8, GRKAN_F32, p) != 0
