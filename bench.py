@@ -29,7 +29,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); the
 # summaries are under profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/bench_kat_b_f32_hbm_traffic.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB, stage 1 + stage 2
+    "kat_b/f32/bwd_x2": 908067 * 1024,
+}
 
 
 def parse_args():
@@ -44,6 +47,8 @@ def parse_args():
                          "kernel moves more than 1.1 GB, i.e. several times the 256 MB last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-kernel table")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch a plain device copy of x2's size (for scaling profiler byte counters)")
     return ap.parse_args()
 
 
@@ -191,6 +196,12 @@ def main():
         "kernel": "grkan_bwd on x2 [%d,%d] (stage 1 + stage 2), %d algorithmic bytes per launch, avg %.2f us"
                   % (l2.rows, l2.D, l2.bwd_bytes(), bwd2_ms * 1e3),
     }
+
+    if args.copy_calibration:
+        # a copy of known size: reads and writes l2.M elements once each
+        for i in range(3):
+            l2.y[i % l2.sets].copy_(l2.x[i % l2.sets])
+        torch.cuda.synchronize()
 
     detail = None
     if not args.no_detail:

@@ -20,6 +20,8 @@
 
 #include <cstdlib>
 #include <mutex>
+#include <tuple>
+#include <vector>
 
 #include "grkan_plan.h"
 
@@ -260,11 +262,12 @@ struct BwdArgs {
     Walk walk;
 };
 
-// Forward.  In fixed-column mode a wave holds one chunk in registers and
-// issues the load of its next chunk as soon as the current one is consumed,
-// before the store.  Deeper per-wave prefetch and more resident waves were
-// both measured slower: this memory system streams best with a few MB of loads
-// in flight chip-wide, and overlap comes from the other waves of the SIMD.
+// Forward.  In fixed-column mode a wave prefetches: the loads of its next chunk
+// are issued before the arithmetic on the current one, so every resident wave
+// always has one chunk of loads in flight.  The persistent grid is then sized
+// so that the chip as a whole keeps about 4 MB of loads in flight (measured
+// optimum of this memory system for a streaming read/write mix; both deeper
+// per-wave prefetch and more resident waves were measured slower).
 template <typename IO, int VEC, bool FIXED>
 __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs a)
 {
@@ -300,13 +303,19 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
         if (n_it > 0)
             load_vec<IO, VEC>(xin(0), xs);
         for (int32_t it = 0; it < n_it; ++it) {
-            float yv[VEC];
+            const bool more = it + 1 < n_it;
+            float xn[VEC], yv[VEC];
+            if (more)
+                load_vec<IO, VEC>(xin(it + 1), xn); // prefetch
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
                 yv[e] = fwd_elem(xs[e], c);
-            if (it + 1 < n_it)
-                load_vec<IO, VEC>(xin(it + 1), xs);
             store_vec<IO, VEC>(yout(it), yv);
+            if (more) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    xs[e] = xn[e];
+            }
         }
         if (tail)
             one(base0 + (uint64_t)(uint32_t)n_it * step + lo);
@@ -369,15 +378,23 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
             load_vec<IO, VEC>(dyin(0), ds);
         }
         for (int32_t it = 0; it < n_it; ++it) {
-            float ov[VEC];
+            const bool more = it + 1 < n_it;
+            float xn[VEC], dn[VEC], ov[VEC];
+            if (more) { // prefetch the next chunk before working on this one
+                load_vec<IO, VEC>(xin(it + 1), xn);
+                load_vec<IO, VEC>(dyin(it + 1), dn);
+            }
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
                 ov[e] = bwd_elem(xs[e], ds[e], c, acc);
-            if (it + 1 < n_it) {
-                load_vec<IO, VEC>(xin(it + 1), xs);
-                load_vec<IO, VEC>(dyin(it + 1), ds);
-            }
             store_vec<IO, VEC>(dxout(it), ov);
+            if (more) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    xs[e] = xn[e];
+                    ds[e] = dn[e];
+                }
+            }
         }
         if (tail)
             one(base0 + (uint64_t)(uint32_t)n_it * step + lo);
@@ -492,13 +509,16 @@ static int env_int(const char *name, int fallback)
     return v > 0 ? v : fallback;
 }
 
-// Workgroups per compute unit the persistent grids are sized for (measured on
-// MI355X at the KAT shapes).  The float32 kernels are bound by HBM and stream
-// fastest with 3 workgroups (12 waves) per unit; the bfloat16 backward pass is
-// bound by the vector ALU and wants every wave slot.  The environment
-// variables override the defaults for experiments.
-static int fwd_wg_per_cu(grkan_dtype_t io) { return env_int("GRKAN_FWD_WG_PER_CU", io == GRKAN_F32 ? 3 : 4); }
-static int bwd_wg_per_cu(grkan_dtype_t io) { return env_int("GRKAN_BWD_WG_PER_CU", io == GRKAN_F32 ? 3 : 8); }
+// Workgroups (of 4 waves) per compute unit the persistent grids are sized for.
+// With one chunk of loads in flight per wave (1 KB forward, 2 KB backward),
+// 4 and 2 workgroups per unit put about 4 MB of loads in flight on 256 units,
+// which is where the HBM-bound kernels were measured fastest.  The bfloat16
+// backward pass moves half the bytes for the same arithmetic and is bound by
+// the vector ALU instead: it takes every wave slot it can get (the request is
+// clamped to the kernel's real occupancy).  The environment variables
+// override the defaults for experiments.
+static int fwd_wg_per_cu(grkan_dtype_t) { return env_int("GRKAN_FWD_WG_PER_CU", 4); }
+static int bwd_wg_per_cu(grkan_dtype_t io) { return env_int("GRKAN_BWD_WG_PER_CU", io == GRKAN_F32 ? 2 : 8); }
 
 static int32_t common_alignment(std::initializer_list<const void *> ptrs)
 {
@@ -508,60 +528,102 @@ static int32_t common_alignment(std::initializer_list<const void *> ptrs)
     return (int32_t)(bits & (~bits + 1)); // lowest set bit, at most 16
 }
 
-template <typename IO, int VEC> static hipError_t launch_fwd(const FwdArgs &a, bool fixed, int grid, hipStream_t st)
+// Kernel selection: the variant for (dtype, vector width, walk mode) as a
+// plain function pointer, so that one code path can both query its occupancy
+// and launch it.
+using FwdKernel = void (*)(const FwdArgs);
+using BwdKernel = void (*)(const BwdArgs);
+
+template <typename IO, int VEC> static FwdKernel fwd_variant(bool fixed)
 {
-    if (fixed)
-        hipLaunchKernelGGL((grkan_fwd_kernel<IO, VEC, true>), dim3(grid), dim3(kThreadsPerWg), 0, st, a);
-    else
-        hipLaunchKernelGGL((grkan_fwd_kernel<IO, VEC, false>), dim3(grid), dim3(kThreadsPerWg), 0, st, a);
-    return hipGetLastError();
+    return fixed ? grkan_fwd_kernel<IO, VEC, true> : grkan_fwd_kernel<IO, VEC, false>;
+}
+template <typename IO, int VEC> static BwdKernel bwd_variant(bool fixed)
+{
+    return fixed ? grkan_bwd_stage1_kernel<IO, VEC, true> : grkan_bwd_stage1_kernel<IO, VEC, false>;
 }
 
-template <typename IO, int VEC> static hipError_t launch_bwd(const BwdArgs &a, bool fixed, int grid, hipStream_t st)
-{
-    if (fixed)
-        hipLaunchKernelGGL((grkan_bwd_stage1_kernel<IO, VEC, true>), dim3(grid), dim3(kThreadsPerWg), 0, st, a);
-    else
-        hipLaunchKernelGGL((grkan_bwd_stage1_kernel<IO, VEC, false>), dim3(grid), dim3(kThreadsPerWg), 0, st, a);
-    return hipGetLastError();
-}
-
-static hipError_t dispatch_fwd(grkan_dtype_t io, int vec, const FwdArgs &a, bool fixed, int grid, hipStream_t st)
+static FwdKernel select_fwd(grkan_dtype_t io, int vec, bool fixed)
 {
     if (io == GRKAN_F32) {
         switch (vec) {
-        case 4: return launch_fwd<float, 4>(a, fixed, grid, st);
-        case 2: return launch_fwd<float, 2>(a, fixed, grid, st);
-        case 1: return launch_fwd<float, 1>(a, fixed, grid, st);
+        case 4: return fwd_variant<float, 4>(fixed);
+        case 2: return fwd_variant<float, 2>(fixed);
+        case 1: return fwd_variant<float, 1>(fixed);
         }
     } else {
         switch (vec) {
-        case 8: return launch_fwd<bf16_t, 8>(a, fixed, grid, st);
-        case 4: return launch_fwd<bf16_t, 4>(a, fixed, grid, st);
-        case 2: return launch_fwd<bf16_t, 2>(a, fixed, grid, st);
-        case 1: return launch_fwd<bf16_t, 1>(a, fixed, grid, st);
+        case 8: return fwd_variant<bf16_t, 8>(fixed);
+        case 4: return fwd_variant<bf16_t, 4>(fixed);
+        case 2: return fwd_variant<bf16_t, 2>(fixed);
+        case 1: return fwd_variant<bf16_t, 1>(fixed);
         }
     }
-    return hipErrorInvalidValue;
+    return nullptr;
 }
 
-static hipError_t dispatch_bwd(grkan_dtype_t io, int vec, const BwdArgs &a, bool fixed, int grid, hipStream_t st)
+static BwdKernel select_bwd(grkan_dtype_t io, int vec, bool fixed)
 {
     if (io == GRKAN_F32) {
         switch (vec) {
-        case 4: return launch_bwd<float, 4>(a, fixed, grid, st);
-        case 2: return launch_bwd<float, 2>(a, fixed, grid, st);
-        case 1: return launch_bwd<float, 1>(a, fixed, grid, st);
+        case 4: return bwd_variant<float, 4>(fixed);
+        case 2: return bwd_variant<float, 2>(fixed);
+        case 1: return bwd_variant<float, 1>(fixed);
         }
     } else {
         switch (vec) {
-        case 8: return launch_bwd<bf16_t, 8>(a, fixed, grid, st);
-        case 4: return launch_bwd<bf16_t, 4>(a, fixed, grid, st);
-        case 2: return launch_bwd<bf16_t, 2>(a, fixed, grid, st);
-        case 1: return launch_bwd<bf16_t, 1>(a, fixed, grid, st);
+        case 8: return bwd_variant<bf16_t, 8>(fixed);
+        case 4: return bwd_variant<bf16_t, 4>(fixed);
+        case 2: return bwd_variant<bf16_t, 2>(fixed);
+        case 1: return bwd_variant<bf16_t, 1>(fixed);
         }
     }
-    return hipErrorInvalidValue;
+    return nullptr;
+}
+
+// Workgroups of a kernel that fit on one compute unit at once (cached per
+// kernel and device).  A persistent grid larger than that would leave
+// workgroups queued behind the resident ones.
+static int resident_wg_per_cu(const void *kernel, int dev)
+{
+    static std::mutex mu;
+    static std::vector<std::tuple<const void *, int, int>> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const auto &e : cache)
+        if (std::get<0>(e) == kernel && std::get<1>(e) == dev)
+            return std::get<2>(e);
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kThreadsPerWg, 0) != hipSuccess || n <= 0)
+        return 0;
+    cache.emplace_back(kernel, dev, n);
+    return n;
+}
+
+// Plans the launch with `want` workgroups per unit, then clamps to what the
+// selected kernel can keep resident and re-plans if needed.
+template <typename Select>
+static grkan_status_t plan_resident(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, int32_t align,
+                                    const DeviceInfo &info, int dev, int want, Select select,
+                                    grkan_plan_t *pl, Walk *walk, const void **kernel)
+{
+    grkan_status_t st = make_plan(rows, D, G, io, align, info.num_cu, want, pl, walk);
+    if (st != GRKAN_OK)
+        return st;
+    *kernel = reinterpret_cast<const void *>(select(io, pl->vec, pl->fixed_col != 0));
+    if (!*kernel)
+        return GRKAN_ERR_LAUNCH;
+    const int fit = resident_wg_per_cu(*kernel, dev);
+    if (fit <= 0)
+        return GRKAN_ERR_LAUNCH;
+    if (fit < want) {
+        st = make_plan(rows, D, G, io, align, info.num_cu, fit, pl, walk);
+        if (st != GRKAN_OK)
+            return st;
+        *kernel = reinterpret_cast<const void *>(select(io, pl->vec, pl->fixed_col != 0));
+        if (!*kernel)
+            return GRKAN_ERR_LAUNCH;
+    }
+    return GRKAN_OK;
 }
 
 static grkan_status_t check_common(int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n, grkan_dtype_t io)
@@ -591,7 +653,9 @@ extern "C" size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, 
     size_t need = 16; // never zero, so that callers can always allocate it
     for (int align = elem_size(io); align <= 16; align *= 2) {
         grkan_plan_t pl;
-        if (make_plan(rows, D, G, io, align, info.num_cu, bwd_wg_per_cu(io), &pl, nullptr) != GRKAN_OK)
+        const void *kernel = nullptr;
+        if (plan_resident(rows, D, G, io, align, info, dev, bwd_wg_per_cu(io), select_bwd, &pl, nullptr, &kernel) !=
+            GRKAN_OK)
             return 0;
         const size_t b = workspace_for(pl, G);
         need = b > need ? b : need;
@@ -621,14 +685,18 @@ extern "C" grkan_status_t grkan_fwd(const void *x, const float *A, const float *
         return GRKAN_ERR_LAUNCH;
     grkan_plan_t pl;
     FwdArgs a;
-    st = make_plan(rows, D, G, io, common_alignment({x, y}), info.num_cu, fwd_wg_per_cu(io), &pl, &a.walk);
+    const void *kernel = nullptr;
+    st = plan_resident(rows, D, G, io, common_alignment({x, y}), info, dev, fwd_wg_per_cu(io), select_fwd, &pl,
+                       &a.walk, &kernel);
     if (st != GRKAN_OK)
         return st;
     a.x = static_cast<const char *>(x);
     a.y = static_cast<char *>(y);
     a.A = A;
     a.B = B;
-    const hipError_t e = dispatch_fwd(io, pl.vec, a, pl.fixed_col != 0, pl.grid, static_cast<hipStream_t>(hip_stream));
+    void *args[] = {&a};
+    const hipError_t e = hipLaunchKernel(kernel, dim3(pl.grid), dim3(kThreadsPerWg), args, 0,
+                                         static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
 }
 
@@ -655,7 +723,9 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
         return GRKAN_ERR_LAUNCH;
     grkan_plan_t pl;
     BwdArgs a;
-    st = make_plan(rows, D, G, io, common_alignment({x, dy, dx}), info.num_cu, bwd_wg_per_cu(io), &pl, &a.walk);
+    const void *kernel = nullptr;
+    st = plan_resident(rows, D, G, io, common_alignment({x, dy, dx}), info, dev, bwd_wg_per_cu(io), select_bwd, &pl,
+                       &a.walk, &kernel);
     if (st != GRKAN_OK)
         return st;
     const size_t need = workspace_for(pl, G);
@@ -670,8 +740,8 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
     a.B = B;
     a.partial = static_cast<float *>(workspace);
     if (pl.grid > 0) {
-        const hipError_t e = dispatch_bwd(io, pl.vec, a, pl.fixed_col != 0, pl.grid, stream);
-        if (e != hipSuccess)
+        void *args[] = {&a};
+        if (hipLaunchKernel(kernel, dim3(pl.grid), dim3(kThreadsPerWg), args, 0, stream) != hipSuccess)
             return GRKAN_ERR_LAUNCH;
     }
     // with no rows there are no workspace rows and stage 2 writes zeros
