@@ -63,22 +63,27 @@ const char *grkan_status_string(grkan_status_t status);
  * Launch geometry the backward (and forward) pass uses for one shape.  Host
  * logic only; exposed so that callers and tests can see how a shape is cut.
  *
- * One wavefront owns one group g and walks that group's [rows x d_g] slab in
- * chunks of 64 vectors; `wg_per_bundle * waves_per_group_in_wg` wavefronts
- * share a group.  A workgroup holds `groups_per_wg` adjacent groups (more than
- * one only when a group's row segment is not a whole number of 128-byte lines).
+ * Two walks exist.  Group walk (lane_coef = 0): one wavefront owns one group g
+ * and walks that group's [rows x d_g] slab in chunks of 64 vectors;
+ * `wg_per_bundle * waves_per_group_in_wg` wavefronts share a group, and a
+ * workgroup holds `groups_per_wg` adjacent groups.  Flat walk (lane_coef = 1),
+ * chosen when a group's row segment is shorter than 384 bytes or not a whole
+ * number of 128-byte lines: wavefronts walk whole rows (the plan is that of a
+ * single group of D channels) and every lane keeps the coefficients of the
+ * group its fixed column belongs to.
  */
 typedef struct {
     int32_t vec;                  /* elements per lane per memory access */
-    int32_t vecs_per_segment;     /* d_g / vec */
+    int32_t vecs_per_segment;     /* d_g / vec (D / vec in the flat walk) */
     int32_t waves_per_wg;         /* wavefronts in a workgroup */
     int32_t groups_per_wg;        /* adjacent groups that share a workgroup */
     int32_t waves_per_group_in_wg;/* waves_per_wg / groups_per_wg */
     int32_t wg_per_bundle;        /* workgroups that share one bundle of groups */
-    int32_t grid;                 /* workgroups launched = (G / groups_per_wg) * wg_per_bundle */
+    int32_t grid;                 /* workgroups launched = (walk groups / groups_per_wg) * wg_per_bundle */
     int32_t fixed_col;            /* 1: every lane keeps its column for the whole kernel */
     int64_t chunk_stride;         /* 64-vector chunks between two visits of one wavefront */
     int32_t partials_per_group;   /* rows of 10 floats each group contributes to the workspace */
+    int32_t lane_coef;            /* 1: flat walk with per-lane coefficients (then fixed_col = 1) */
 } grkan_plan_t;
 
 /*

@@ -40,6 +40,7 @@ class Plan(ctypes.Structure):
         ("fixed_col", ctypes.c_int32),
         ("chunk_stride", ctypes.c_int64),
         ("partials_per_group", ctypes.c_int32),
+        ("lane_coef", ctypes.c_int32),
     ]
 
     def as_dict(self):

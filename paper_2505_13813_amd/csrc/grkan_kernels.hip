@@ -249,6 +249,7 @@ struct FwdArgs {
     char *y;
     const float *A;
     const float *B;
+    int32_t dgc; // channels per coefficient group (differs from walk.dg in the flat walk)
     Walk walk;
 };
 
@@ -258,7 +259,9 @@ struct BwdArgs {
     char *dx;
     const float *A;
     const float *B;
-    float *partial; // [G][wg_per_bundle][10]
+    float *partial; // [G][rows_per_group][10]
+    int32_t Gc;     // coefficient groups
+    int32_t dgc;    // channels per coefficient group (differs from walk.dg in the flat walk)
     Walk walk;
 };
 
@@ -268,14 +271,18 @@ struct BwdArgs {
 // so that the chip as a whole keeps about 4 MB of loads in flight (measured
 // optimum of this memory system for a streaming read/write mix; both deeper
 // per-wave prefetch and more resident waves were measured slower).
-template <typename IO, int VEC, bool FIXED>
+template <typename IO, int VEC, bool FIXED, bool LANECOEF>
 __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs a)
 {
+    static_assert(FIXED || !LANECOEF, "per-lane coefficients need fixed columns");
     const Walk &p = a.walk;
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
-    const Coef c = load_coef(a.A, a.B, id.g);
+    // group walk: the wave's group (scalar registers); flat walk: the group of
+    // this lane's fixed column (vector registers)
+    const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc) : id.g;
+    const Coef c = load_coef(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
     constexpr int64_t ES = sizeof(IO);
@@ -331,16 +338,16 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
 }
 
 // Backward, stage 1 (see the file header).
-template <typename IO, int VEC, bool FIXED>
+template <typename IO, int VEC, bool FIXED, bool LANECOEF>
 __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const BwdArgs a)
 {
-    __shared__ float wave_part[kWavesPerWg][kNumCoef];
-
+    static_assert(FIXED || !LANECOEF, "per-lane coefficients need fixed columns");
     const Walk &p = a.walk;
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
-    const Coef c = load_coef(a.A, a.B, id.g);
+    const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc) : id.g;
+    const Coef c = load_coef(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
     constexpr int64_t ES = sizeof(IO);
@@ -408,38 +415,82 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
             one((uint64_t)(elem_offset(p, id.g, s) * ES));
     }
 
-    // registers -> wavefront (DPP) -> workgroup (LDS) -> one workspace row per group
+    if constexpr (!LANECOEF) {
+        // registers -> wavefront (DPP) -> workgroup (LDS) -> one workspace row per group
+        __shared__ float wave_part[kWavesPerWg][kNumCoef];
 #pragma unroll
-    for (int k = 0; k < kNumCoef; ++k) {
-        const float s = wave_sum(acc[k]);
-        if (lane == 0)
-            wave_part[wv][k] = s;
-    }
-    __syncthreads();
-    const int tid = threadIdx.x;
-    if (tid < p.k * kNumCoef) {
-        const int gl = tid / kNumCoef;
-        const int kc = tid - gl * kNumCoef;
-        // waves gl, gl + k, gl + 2k, ... of this workgroup hold group (bundle * k + gl)
-        float s = 0.0f;
-        for (int sub = 0; sub < p.ns; ++sub)
-            s += wave_part[sub * p.k + gl][kc];
-        const int32_t bundle = (int32_t)blockIdx.x % p.nb;
-        const int32_t wgi = (int32_t)blockIdx.x / p.nb;
-        const int64_t g = (int64_t)bundle * p.k + gl;
-        a.partial[(g * p.wg_per_bundle + wgi) * kNumCoef + kc] = s;
+        for (int k = 0; k < kNumCoef; ++k) {
+            const float s = wave_sum(acc[k]);
+            if (lane == 0)
+                wave_part[wv][k] = s;
+        }
+        __syncthreads();
+        const int tid = threadIdx.x;
+        if (tid < p.k * kNumCoef) {
+            const int gl = tid / kNumCoef;
+            const int kc = tid - gl * kNumCoef;
+            // waves gl, gl + k, gl + 2k, ... of this workgroup hold group (bundle * k + gl)
+            float s = 0.0f;
+            for (int sub = 0; sub < p.ns; ++sub)
+                s += wave_part[sub * p.k + gl][kc];
+            const int32_t bundle = (int32_t)blockIdx.x % p.nb;
+            const int32_t wgi = (int32_t)blockIdx.x / p.nb;
+            const int64_t g = (int64_t)bundle * p.k + gl;
+            a.partial[(g * p.wg_per_bundle + wgi) * kNumCoef + kc] = s;
+        }
+    } else {
+        // Flat walk: the 256 lanes of the workgroup hold consecutive vectors of
+        // the rows, so lanes of one coefficient group form runs of vt = d_g / vec
+        // lanes (a group can own several runs when a row is shorter than the
+        // workgroup).  registers -> LDS -> one sum per run (fixed lane order) ->
+        // one sum per group (fixed run order) -> one workspace row per group and
+        // workgroup, zeros included, so that stage 2 needs no map of who wrote what.
+        __shared__ float lane_part[kNumCoef][kThreadsPerWg];
+        __shared__ float run_part[kThreadsPerWg + 1][kNumCoef];
+        const int tid = threadIdx.x;
+#pragma unroll
+        for (int k = 0; k < kNumCoef; ++k)
+            lane_part[k][tid] = acc[k];
+        __syncthreads();
+        const uint32_t vt = (uint32_t)a.dgc / (uint32_t)p.vec; // lanes per run
+        const uint32_t V = (uint32_t)p.v;                       // vectors per row
+        const uint32_t c0 = ((uint32_t)blockIdx.x * kThreadsPerWg) % V; // column of lane 0
+        const uint32_t u0 = c0 / vt;                            // first (unwrapped) run
+        const uint32_t n_runs = (c0 + kThreadsPerWg - 1) / vt - u0 + 1;
+        for (uint32_t item = tid; item < n_runs * kNumCoef; item += kThreadsPerWg) {
+            const uint32_t r = item / kNumCoef, k = item - r * kNumCoef;
+            const uint32_t first = (u0 + r) * vt; // unwrapped column where run r starts
+            const uint32_t lo = first > c0 ? first - c0 : 0;
+            const uint32_t hi = first + vt - c0 < (uint32_t)kThreadsPerWg ? first + vt - c0 : (uint32_t)kThreadsPerWg;
+            float s = 0.0f;
+            for (uint32_t l = lo; l < hi; ++l)
+                s += lane_part[k][l];
+            run_part[r][k] = s;
+        }
+        __syncthreads();
+        const uint32_t G = (uint32_t)a.Gc;
+        for (uint32_t item = tid; item < G * kNumCoef; item += kThreadsPerWg) {
+            const uint32_t g = item / kNumCoef, k = item - g * kNumCoef;
+            // run r belongs to group (u0 + r) mod G
+            float s = 0.0f;
+            for (uint32_t r = (g + G - u0 % G) % G; r < n_runs; r += G)
+                s += run_part[r][k];
+            a.partial[((int64_t)g * gridDim.x + blockIdx.x) * kNumCoef + k] = s;
+        }
     }
 }
 
-// One workgroup per group: fixed-order sum of the group's workspace rows.
-constexpr int kStage2Threads = 256;
+// Stage 2.  One wavefront per group: lane l adds the group's workspace rows
+// l, l + 64, ... in double, the 64 lane sums go through LDS, and ten lanes add
+// them in lane order.  Every order is fixed; dA / dB are overwritten.
+constexpr int kStage2Threads = kWave;
 
 __global__ __launch_bounds__(kStage2Threads) void grkan_bwd_stage2_kernel(const float *__restrict__ partial,
                                                                           int32_t rows_per_group,
                                                                           float *__restrict__ dA,
                                                                           float *__restrict__ dB)
 {
-    __shared__ double red[kStage2Threads][kNumCoef];
+    __shared__ double lane_sum[kNumCoef][kStage2Threads];
     const int g = blockIdx.x;
     const int tid = threadIdx.x;
     const float *base = partial + (size_t)g * rows_per_group * kNumCoef;
@@ -455,20 +506,17 @@ __global__ __launch_bounds__(kStage2Threads) void grkan_bwd_stage2_kernel(const 
     }
 #pragma unroll
     for (int k = 0; k < kNumCoef; ++k)
-        red[tid][k] = s[k];
+        lane_sum[k][tid] = s[k];
     __syncthreads();
-    for (int half = kStage2Threads / 2; half > 0; half >>= 1) {
-        if (tid < half) {
-#pragma unroll
-            for (int k = 0; k < kNumCoef; ++k)
-                red[tid][k] += red[tid + half][k];
-        }
-        __syncthreads();
+    if (tid < kNumCoef) {
+        double t = 0.0;
+        for (int l = 0; l < kStage2Threads; ++l)
+            t += lane_sum[tid][l];
+        if (tid < 6)
+            dA[g * 6 + tid] = (float)t;
+        else
+            dB[g * 4 + (tid - 6)] = (float)t;
     }
-    if (tid < 6)
-        dA[g * 6 + tid] = (float)red[0][tid];
-    else if (tid < kNumCoef)
-        dB[g * 4 + (tid - 6)] = (float)red[0][tid];
 }
 
 // --------------------------------------------------------------------------
@@ -509,17 +557,6 @@ static int env_int(const char *name, int fallback)
     return v > 0 ? v : fallback;
 }
 
-// Workgroups (of 4 waves) per compute unit the persistent grids are sized for.
-// With one chunk of loads in flight per wave (1 KB forward, 2 KB backward),
-// 4 and 2 workgroups per unit put about 4 MB of loads in flight on 256 units,
-// which is where the HBM-bound kernels were measured fastest.  The bfloat16
-// backward pass moves half the bytes for the same arithmetic and is bound by
-// the vector ALU instead: it takes every wave slot it can get (the request is
-// clamped to the kernel's real occupancy).  The environment variables
-// override the defaults for experiments.
-static int fwd_wg_per_cu(grkan_dtype_t) { return env_int("GRKAN_FWD_WG_PER_CU", 4); }
-static int bwd_wg_per_cu(grkan_dtype_t io) { return env_int("GRKAN_BWD_WG_PER_CU", io == GRKAN_F32 ? 2 : 8); }
-
 static int32_t common_alignment(std::initializer_list<const void *> ptrs)
 {
     uintptr_t bits = 16;
@@ -534,48 +571,52 @@ static int32_t common_alignment(std::initializer_list<const void *> ptrs)
 using FwdKernel = void (*)(const FwdArgs);
 using BwdKernel = void (*)(const BwdArgs);
 
-template <typename IO, int VEC> static FwdKernel fwd_variant(bool fixed)
+template <typename IO, int VEC> static FwdKernel fwd_variant(bool fixed, bool lane_coef)
 {
-    return fixed ? grkan_fwd_kernel<IO, VEC, true> : grkan_fwd_kernel<IO, VEC, false>;
+    if (lane_coef)
+        return grkan_fwd_kernel<IO, VEC, true, true>;
+    return fixed ? grkan_fwd_kernel<IO, VEC, true, false> : grkan_fwd_kernel<IO, VEC, false, false>;
 }
-template <typename IO, int VEC> static BwdKernel bwd_variant(bool fixed)
+template <typename IO, int VEC> static BwdKernel bwd_variant(bool fixed, bool lane_coef)
 {
-    return fixed ? grkan_bwd_stage1_kernel<IO, VEC, true> : grkan_bwd_stage1_kernel<IO, VEC, false>;
+    if (lane_coef)
+        return grkan_bwd_stage1_kernel<IO, VEC, true, true>;
+    return fixed ? grkan_bwd_stage1_kernel<IO, VEC, true, false> : grkan_bwd_stage1_kernel<IO, VEC, false, false>;
 }
 
-static FwdKernel select_fwd(grkan_dtype_t io, int vec, bool fixed)
+static FwdKernel select_fwd(grkan_dtype_t io, int vec, bool fixed, bool lane_coef)
 {
     if (io == GRKAN_F32) {
         switch (vec) {
-        case 4: return fwd_variant<float, 4>(fixed);
-        case 2: return fwd_variant<float, 2>(fixed);
-        case 1: return fwd_variant<float, 1>(fixed);
+        case 4: return fwd_variant<float, 4>(fixed, lane_coef);
+        case 2: return fwd_variant<float, 2>(fixed, lane_coef);
+        case 1: return fwd_variant<float, 1>(fixed, lane_coef);
         }
     } else {
         switch (vec) {
-        case 8: return fwd_variant<bf16_t, 8>(fixed);
-        case 4: return fwd_variant<bf16_t, 4>(fixed);
-        case 2: return fwd_variant<bf16_t, 2>(fixed);
-        case 1: return fwd_variant<bf16_t, 1>(fixed);
+        case 8: return fwd_variant<bf16_t, 8>(fixed, lane_coef);
+        case 4: return fwd_variant<bf16_t, 4>(fixed, lane_coef);
+        case 2: return fwd_variant<bf16_t, 2>(fixed, lane_coef);
+        case 1: return fwd_variant<bf16_t, 1>(fixed, lane_coef);
         }
     }
     return nullptr;
 }
 
-static BwdKernel select_bwd(grkan_dtype_t io, int vec, bool fixed)
+static BwdKernel select_bwd(grkan_dtype_t io, int vec, bool fixed, bool lane_coef)
 {
     if (io == GRKAN_F32) {
         switch (vec) {
-        case 4: return bwd_variant<float, 4>(fixed);
-        case 2: return bwd_variant<float, 2>(fixed);
-        case 1: return bwd_variant<float, 1>(fixed);
+        case 4: return bwd_variant<float, 4>(fixed, lane_coef);
+        case 2: return bwd_variant<float, 2>(fixed, lane_coef);
+        case 1: return bwd_variant<float, 1>(fixed, lane_coef);
         }
     } else {
         switch (vec) {
-        case 8: return bwd_variant<bf16_t, 8>(fixed);
-        case 4: return bwd_variant<bf16_t, 4>(fixed);
-        case 2: return bwd_variant<bf16_t, 2>(fixed);
-        case 1: return bwd_variant<bf16_t, 1>(fixed);
+        case 8: return bwd_variant<bf16_t, 8>(fixed, lane_coef);
+        case 4: return bwd_variant<bf16_t, 4>(fixed, lane_coef);
+        case 2: return bwd_variant<bf16_t, 2>(fixed, lane_coef);
+        case 1: return bwd_variant<bf16_t, 1>(fixed, lane_coef);
         }
     }
     return nullptr;
@@ -599,28 +640,67 @@ static int resident_wg_per_cu(const void *kernel, int dev)
     return n;
 }
 
-// Plans the launch with `want` workgroups per unit, then clamps to what the
-// selected kernel can keep resident and re-plans if needed.
+// Workgroups (of 4 waves) per compute unit the persistent grids are sized for.
+// With one chunk of loads in flight per wave (1 KB forward, 2 KB backward),
+// 4 and 2 workgroups per unit put about 4 MB of loads in flight on 256 units,
+// which is where the HBM-bound kernels were measured fastest (the flat walk's
+// backward pass, with its coefficients in vector registers and a longer
+// epilogue, measured best at 3).  The bfloat16 backward pass moves half the
+// bytes for the same arithmetic and is bound by the vector ALU instead: it
+// takes every wave slot it can get (requests are clamped to the kernel's real
+// occupancy).  The environment variables override both walks for experiments.
+struct Want {
+    int group_walk;
+    int flat_walk;
+};
+
+static Want fwd_want(grkan_dtype_t)
+{
+    const int e = env_int("GRKAN_FWD_WG_PER_CU", 0);
+    return e ? Want{e, e} : Want{4, 4};
+}
+
+static Want bwd_want(grkan_dtype_t io)
+{
+    const int e = env_int("GRKAN_BWD_WG_PER_CU", 0);
+    if (e)
+        return Want{e, e};
+    return io == GRKAN_F32 ? Want{2, 3} : Want{8, 8};
+}
+
+// Plans the launch with the wanted workgroups per unit, then clamps to what
+// the selected kernel can keep resident and re-plans if needed.
 template <typename Select>
 static grkan_status_t plan_resident(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, int32_t align,
-                                    const DeviceInfo &info, int dev, int want, Select select,
+                                    const DeviceInfo &info, int dev, Want want, Select select,
                                     grkan_plan_t *pl, Walk *walk, const void **kernel)
 {
-    grkan_status_t st = make_plan(rows, D, G, io, align, info.num_cu, want, pl, walk);
+    int per_cu = want.group_walk;
+    grkan_status_t st = make_plan(rows, D, G, io, align, info.num_cu, per_cu, pl, walk);
     if (st != GRKAN_OK)
         return st;
-    *kernel = reinterpret_cast<const void *>(select(io, pl->vec, pl->fixed_col != 0));
+    if (pl->lane_coef && want.flat_walk != per_cu) {
+        grkan_plan_t alt;
+        if (make_plan(rows, D, G, io, align, info.num_cu, want.flat_walk, &alt, nullptr) == GRKAN_OK && alt.lane_coef) {
+            per_cu = want.flat_walk;
+            st = make_plan(rows, D, G, io, align, info.num_cu, per_cu, pl, walk);
+            if (st != GRKAN_OK)
+                return st;
+        }
+    }
+    *kernel = reinterpret_cast<const void *>(select(io, pl->vec, pl->fixed_col != 0, pl->lane_coef != 0));
     if (!*kernel)
         return GRKAN_ERR_LAUNCH;
     const int fit = resident_wg_per_cu(*kernel, dev);
     if (fit <= 0)
         return GRKAN_ERR_LAUNCH;
-    if (fit < want) {
+    if (fit < per_cu) {
+        const int32_t was_flat = pl->lane_coef;
         st = make_plan(rows, D, G, io, align, info.num_cu, fit, pl, walk);
         if (st != GRKAN_OK)
             return st;
-        *kernel = reinterpret_cast<const void *>(select(io, pl->vec, pl->fixed_col != 0));
-        if (!*kernel)
+        *kernel = reinterpret_cast<const void *>(select(io, pl->vec, pl->fixed_col != 0, pl->lane_coef != 0));
+        if (!*kernel || (pl->lane_coef != was_flat && resident_wg_per_cu(*kernel, dev) <= 0))
             return GRKAN_ERR_LAUNCH;
     }
     return GRKAN_OK;
@@ -654,7 +734,7 @@ extern "C" size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, 
     for (int align = elem_size(io); align <= 16; align *= 2) {
         grkan_plan_t pl;
         const void *kernel = nullptr;
-        if (plan_resident(rows, D, G, io, align, info, dev, bwd_wg_per_cu(io), select_bwd, &pl, nullptr, &kernel) !=
+        if (plan_resident(rows, D, G, io, align, info, dev, bwd_want(io), select_bwd, &pl, nullptr, &kernel) !=
             GRKAN_OK)
             return 0;
         const size_t b = workspace_for(pl, G);
@@ -686,7 +766,7 @@ extern "C" grkan_status_t grkan_fwd(const void *x, const float *A, const float *
     grkan_plan_t pl;
     FwdArgs a;
     const void *kernel = nullptr;
-    st = plan_resident(rows, D, G, io, common_alignment({x, y}), info, dev, fwd_wg_per_cu(io), select_fwd, &pl,
+    st = plan_resident(rows, D, G, io, common_alignment({x, y}), info, dev, fwd_want(io), select_fwd, &pl,
                        &a.walk, &kernel);
     if (st != GRKAN_OK)
         return st;
@@ -694,6 +774,7 @@ extern "C" grkan_status_t grkan_fwd(const void *x, const float *A, const float *
     a.y = static_cast<char *>(y);
     a.A = A;
     a.B = B;
+    a.dgc = D / G;
     void *args[] = {&a};
     const hipError_t e = hipLaunchKernel(kernel, dim3(pl.grid), dim3(kThreadsPerWg), args, 0,
                                          static_cast<hipStream_t>(hip_stream));
@@ -724,7 +805,7 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
     grkan_plan_t pl;
     BwdArgs a;
     const void *kernel = nullptr;
-    st = plan_resident(rows, D, G, io, common_alignment({x, dy, dx}), info, dev, bwd_wg_per_cu(io), select_bwd, &pl,
+    st = plan_resident(rows, D, G, io, common_alignment({x, dy, dx}), info, dev, bwd_want(io), select_bwd, &pl,
                        &a.walk, &kernel);
     if (st != GRKAN_OK)
         return st;
@@ -739,6 +820,8 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
     a.A = A;
     a.B = B;
     a.partial = static_cast<float *>(workspace);
+    a.Gc = G;
+    a.dgc = D / G;
     if (pl.grid > 0) {
         void *args[] = {&a};
         if (hipLaunchKernel(kernel, dim3(pl.grid), dim3(kThreadsPerWg), args, 0, stream) != hipSuccess)

@@ -30,20 +30,12 @@ static int pick_vec(int32_t dg, int es, int32_t align_bytes)
     return 1;
 }
 
-grkan_status_t make_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, int32_t align_bytes,
-                         int32_t num_cu, int32_t wg_per_cu, grkan_plan_t *out, Walk *walk)
+// Plan of the group walk over `Gw` groups of `dgw` channels with vectors of
+// `vec` elements (Gw = 1, dgw = D describes the flat walk over whole rows).
+static grkan_status_t plan_walk(int64_t rows, int32_t D, int32_t Gw, int32_t vec, int es, int32_t num_cu,
+                                int32_t wg_per_cu, grkan_plan_t *out)
 {
-    grkan_status_t st = check_shape(rows, D, G, io);
-    if (st != GRKAN_OK)
-        return st;
-    if (!out)
-        return GRKAN_ERR_NULL;
-    const int es = elem_size(io);
-    if (align_bytes < es || num_cu <= 0 || wg_per_cu <= 0)
-        return GRKAN_ERR_ALIGN;
-
-    const int32_t dg = D / G;
-    const int32_t vec = pick_vec(dg, es, align_bytes);
+    const int32_t dg = D / Gw;
     const int32_t v = dg / vec;
     const int32_t nw = kWavesPerWg;
 
@@ -51,10 +43,10 @@ grkan_status_t make_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, i
     // whole number of cache lines, so that the waves touching the two halves
     // of a line sit on the same compute unit (and the same XCD's L2).
     int32_t k = 1;
-    while (((int64_t)k * dg * es) % kLineBytes != 0 && 2 * k <= nw && G % (2 * k) == 0)
+    while (((int64_t)k * dg * es) % kLineBytes != 0 && 2 * k <= nw && Gw % (2 * k) == 0)
         k *= 2;
     const int32_t ns = nw / k;
-    const int32_t nb = G / k;
+    const int32_t nb = Gw / k;
 
     const int64_t n_vec = rows * (int64_t)v;          // vectors per group
     const int64_t n_chunks = (n_vec + kWave - 1) / kWave;
@@ -86,7 +78,6 @@ grkan_status_t make_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, i
     if (wpb * nb > INT32_MAX || wpb * ns >= ((int64_t)1 << 25))
         return GRKAN_ERR_UNSUPPORTED;
 
-    const int64_t Wg = wpb * ns;
     out->vec = vec;
     out->vecs_per_segment = v;
     out->waves_per_wg = nw;
@@ -95,9 +86,47 @@ grkan_status_t make_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, i
     out->wg_per_bundle = (int32_t)wpb;
     out->grid = (int32_t)(wpb * nb);
     out->fixed_col = fixed;
-    out->chunk_stride = Wg;
+    out->chunk_stride = wpb * ns;
     out->partials_per_group = (int32_t)wpb;
+    out->lane_coef = 0;
+    return GRKAN_OK;
+}
 
+grkan_status_t make_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, int32_t align_bytes,
+                         int32_t num_cu, int32_t wg_per_cu, grkan_plan_t *out, Walk *walk)
+{
+    grkan_status_t st = check_shape(rows, D, G, io);
+    if (st != GRKAN_OK)
+        return st;
+    if (!out)
+        return GRKAN_ERR_NULL;
+    const int es = elem_size(io);
+    if (align_bytes < es || num_cu <= 0 || wg_per_cu <= 0)
+        return GRKAN_ERR_ALIGN;
+
+    const int32_t dg = D / G;
+    const int32_t vec = pick_vec(dg, es, align_bytes);
+
+    // Wavefronts bound to one group read that group's row segments; measured on
+    // MI355X this streams at full speed for segments of 384 bytes and more but
+    // loses 18 % at 192 bytes and 40 % at 96 bytes.  Short or line-straddling
+    // segments therefore take the flat walk over whole rows (if its columns can
+    // be fixed), with the coefficients held per lane.
+    const int64_t seg_bytes = (int64_t)dg * es;
+    const bool short_segments = G > 1 && (seg_bytes < 3 * kLineBytes || seg_bytes % kLineBytes != 0);
+    if (short_segments && rows > 0) {
+        st = plan_walk(rows, D, 1, vec, es, num_cu, wg_per_cu, out);
+        if (st == GRKAN_OK && out->fixed_col) {
+            out->lane_coef = 1;
+            out->partials_per_group = out->grid; // every workgroup writes one row per group
+            if (walk)
+                return walk_from_plan(rows, D, G, io, *out, walk);
+            return GRKAN_OK;
+        }
+    }
+    st = plan_walk(rows, D, G, vec, es, num_cu, wg_per_cu, out);
+    if (st != GRKAN_OK)
+        return st;
     if (walk)
         return walk_from_plan(rows, D, G, io, *out, walk);
     return GRKAN_OK;
@@ -109,20 +138,24 @@ grkan_status_t walk_from_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t 
     grkan_status_t st = check_shape(rows, D, G, io);
     if (st != GRKAN_OK)
         return st;
-    const int32_t dg = D / G;
-    if (pl.vec <= 0 || dg % pl.vec != 0 || pl.vecs_per_segment != dg / pl.vec || pl.groups_per_wg <= 0 ||
-        G % pl.groups_per_wg != 0 || pl.waves_per_wg % pl.groups_per_wg != 0 ||
-        pl.waves_per_group_in_wg != pl.waves_per_wg / pl.groups_per_wg || pl.wg_per_bundle < 0)
+    if (pl.vec <= 0 || (D / G) % pl.vec != 0)
+        return GRKAN_ERR_SHAPE;
+    const int32_t Gw = pl.lane_coef ? 1 : G; // groups of the walk
+    const int32_t dg = D / Gw;
+    if (pl.vecs_per_segment != dg / pl.vec || pl.groups_per_wg <= 0 ||
+        Gw % pl.groups_per_wg != 0 || pl.waves_per_wg != kWavesPerWg || pl.waves_per_wg % pl.groups_per_wg != 0 ||
+        pl.waves_per_group_in_wg != pl.waves_per_wg / pl.groups_per_wg || pl.wg_per_bundle < 0 ||
+        (pl.lane_coef && !pl.fixed_col))
         return GRKAN_ERR_SHAPE;
     walk->rows = rows;
     walk->D = D;
-    walk->G = G;
+    walk->G = Gw;
     walk->dg = dg;
     walk->vec = pl.vec;
     walk->v = pl.vecs_per_segment;
     walk->k = pl.groups_per_wg;
     walk->ns = pl.waves_per_group_in_wg;
-    walk->nb = G / pl.groups_per_wg;
+    walk->nb = Gw / pl.groups_per_wg;
     walk->wg_per_bundle = pl.wg_per_bundle;
     const int64_t Wg = (int64_t)pl.wg_per_bundle * walk->ns;
     if (Wg >= ((int64_t)1 << 25))

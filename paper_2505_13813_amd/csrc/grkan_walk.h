@@ -12,6 +12,11 @@
 // When 64 * Wg is a multiple of v ("fixed column" mode, which the host plan
 // arranges whenever it can) a lane keeps its column and its row offset inside
 // the chunk for the whole kernel and only a wave-uniform base advances.
+//
+// The same walk with a single group of D channels is the "flat" walk over
+// whole rows: wavefronts then read contiguous kilobytes whatever d_g is, and
+// because columns are fixed each lane belongs to one coefficient group for the
+// whole kernel and keeps that group's coefficients in vector registers.
 #ifndef GRKAN_WALK_H_
 #define GRKAN_WALK_H_
 
@@ -138,14 +143,28 @@ GRKAN_HD int64_t fixed_base0(const Walk &p, int32_t g, int32_t w)
 
 GRKAN_HD int64_t fixed_step(const Walk &p) { return (int64_t)p.dq * p.D; }
 
-GRKAN_HD uint32_t fixed_lane_offset(const Walk &p, int32_t w, int32_t lane)
+// Column (in vectors, inside the walk group's row segment) a lane keeps in
+// fixed-column mode, and the rows it sits below the chunk's first row.
+struct LaneCol {
+    uint32_t rrow;
+    uint32_t ccol;
+};
+
+GRKAN_HD LaneCol fixed_lane_col(const Walk &p, int32_t w, int32_t lane)
 {
     const uint32_t row0 = (uint32_t)GRKAN_UNIFORM(((uint32_t)w * kWave) / (uint32_t)p.v);
     const uint32_t c0 = (uint32_t)w * kWave - row0 * (uint32_t)p.v;
     const uint32_t cl = c0 + (uint32_t)lane;
-    const uint32_t rrow = cl / (uint32_t)p.v;
-    const uint32_t ccol = cl - rrow * (uint32_t)p.v;
-    return rrow * (uint32_t)p.D + ccol * (uint32_t)p.vec;
+    LaneCol lc;
+    lc.rrow = cl / (uint32_t)p.v;
+    lc.ccol = cl - lc.rrow * (uint32_t)p.v;
+    return lc;
+}
+
+GRKAN_HD uint32_t fixed_lane_offset(const Walk &p, int32_t w, int32_t lane)
+{
+    const LaneCol lc = fixed_lane_col(p, w, lane);
+    return lc.rrow * (uint32_t)p.D + lc.ccol * (uint32_t)p.vec;
 }
 
 } // namespace grkan

@@ -42,9 +42,9 @@ def test_tiny_config_elementwise(oracle, dtype):
 # ------------------------------------------------------------------ shapes that span tiles, tails, vector widths
 SHAPES = [
     # rows, D, G            what it exercises
-    (1000, 192, 8),       # KAT-T x1 segment (96 B): 4 groups per workgroup, ragged tail
+    (1000, 192, 8),       # KAT-T x1 segment (96 B): flat walk, ragged tail
     (999, 768, 8),        # KAT-T x2 / KAT-B x1 segment, odd row count
-    (513, 384, 8),        # KAT-S x1: 2 groups per workgroup
+    (513, 384, 8),        # KAT-S x1 (192 B segments): flat walk
     (257, 1536, 8),       # KAT-S x2
     (301, 3072, 8),       # KAT-B x2 segment
     (129, 3072, 1),       # one group
@@ -53,7 +53,10 @@ SHAPES = [
     (33, 30, 5),          # d_g = 6  -> 2-wide vectors (fp32)
     (29, 35, 5),          # d_g = 7  -> scalar path
     (1, 192, 8), (2, 8, 8), (5, 7, 1), (64, 64, 1), (1, 1, 1),
-    (3, 64 * 4 * 1009, 64),  # general (non fixed-column) walk
+    (3, 64 * 4 * 1009, 64),   # flat walk over very long rows
+    (3, 64 * 64 * 1031, 64),  # group walk, general (non fixed-column) columns
+    (3, 8 * 24 * 10007, 8),   # group walk, 4 groups per workgroup, general columns
+    (700, 192, 48), (300, 96, 96),  # d_g = 4 and d_g = 1: many groups per workgroup in the flat walk
 ]
 
 

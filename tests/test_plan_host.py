@@ -10,7 +10,7 @@ from paper_2505_13813_amd import GRKAN_BF16, GRKAN_F32
 # (rows, D, G) of every configuration the bench and parity tests use, cut to a
 # size the simulator walks in well under a second, plus awkward shapes
 SHAPES = [
-    (788, 192, 8),      # tiny config: 96-byte segments -> 4 groups per workgroup
+    (788, 192, 8),      # tiny config: 96-byte segments -> flat walk
     (1000, 768, 8),     # KAT-T x2 / KAT-B x1
     (300, 384, 8), (300, 1536, 8), (301, 3072, 8),
     (130, 3072, 1), (130, 3072, 64),
@@ -25,16 +25,29 @@ def test_walk_covers_every_vector_exactly_once(rows, D, G, io):
     es = 4 if io == GRKAN_F32 else 2
     for align, (num_cu, wg_per_cu) in itertools.product((16, 8, es), ((256, 4), (256, 8), (3, 1))):
         p = grkan.plan(rows, D, G, io, align_bytes=align, num_cu=num_cu, wg_per_cu=wg_per_cu)
-        assert p.grid == (G // p.groups_per_wg) * p.wg_per_bundle
+        walk_groups = 1 if p.lane_coef else G
+        assert p.grid == (walk_groups // p.groups_per_wg) * p.wg_per_bundle
+        assert not p.lane_coef or p.fixed_col
         assert p.vec * es <= align and (D // G) % p.vec == 0
         assert grkan.plan_cover_errors(rows, D, G, io, p) == 0, p.as_dict()
 
 
 def test_general_walk_is_used_when_columns_cannot_be_fixed_and_still_covers():
-    # d_g = 4 * 1009: 64 * (waves per group) is never a multiple of 1009 within the grid budget
-    rows, G, dg = 3, 64, 4 * 1009
+    # d_g = 64 * 1031 (line-aligned segments, so the group walk is chosen): 64 * (waves per group)
+    # is never a multiple of d_g / vec within the grid budget
+    rows, G, dg = 3, 64, 64 * 1031
+    for io in (GRKAN_F32, GRKAN_BF16):
+        p = grkan.plan(rows, G * dg, G, io)
+        assert (p.fixed_col, p.lane_coef, p.groups_per_wg) == (0, 0, 1)
+        assert grkan.plan_cover_errors(rows, G * dg, G, io, p) == 0
+
+
+def test_group_walk_bundles_groups_when_the_flat_walk_cannot_fix_columns():
+    # 96-byte-misaligned segments (d_g = 24 * 10007) whose rows are too long for the flat walk to
+    # keep columns fixed: group walk, 4 adjacent groups per workgroup, general columns
+    rows, G, dg = 3, 8, 24 * 10007
     p = grkan.plan(rows, G * dg, G, GRKAN_F32)
-    assert p.fixed_col == 0
+    assert (p.fixed_col, p.lane_coef, p.groups_per_wg, p.waves_per_group_in_wg) == (0, 0, 4, 1)
     assert grkan.plan_cover_errors(rows, G * dg, G, GRKAN_F32, p) == 0
 
 
@@ -46,9 +59,13 @@ def test_headline_plans():
     assert (p.vec, p.groups_per_wg, p.waves_per_group_in_wg, p.fixed_col) == (4, 1, 4, 1)
     assert p.grid <= 256 * 4 and p.grid >= 256 * 4 * 0.95
     assert (64 * p.chunk_stride) % p.vecs_per_segment == 0
-    # KAT-B x1 bf16: 192-byte segments -> two adjacent groups per workgroup
+    # KAT-B x1 bf16: 192-byte segments -> flat walk over whole rows, coefficients per lane
     p = grkan.plan(25216, 768, 8, GRKAN_BF16)
-    assert (p.vec, p.groups_per_wg, p.fixed_col) == (8, 2, 1)
+    assert (p.vec, p.lane_coef, p.fixed_col, p.vecs_per_segment) == (8, 1, 1, 96)
+    assert p.partials_per_group == p.grid
+    # stress with 64 groups of 48 channels: flat walk as well
+    p = grkan.plan(50432, 3072, 64, GRKAN_F32)
+    assert p.lane_coef == 1
     # stress, one group
     p = grkan.plan(50432, 3072, 1, GRKAN_F32)
     assert p.groups_per_wg == 1 and p.fixed_col == 1
@@ -77,9 +94,9 @@ def test_plan_rejects_bad_arguments(rows, D, G, io, status):
 
 
 def test_a_corrupted_plan_fails_the_cover_check():
-    p = grkan.plan(100, 192, 8, GRKAN_F32)
+    p = grkan.plan(100, 768, 8, GRKAN_F32)
     p.wg_per_bundle -= 3  # fewer waves but the same stride bookkeeping: still a cover
-    assert grkan.plan_cover_errors(100, 192, 8, GRKAN_F32, p) == 0
+    assert grkan.plan_cover_errors(100, 768, 8, GRKAN_F32, p) == 0
     p.fixed_col = 1
     p.wg_per_bundle += 1  # 64 * waves is no longer a multiple of the segment length
-    assert grkan.plan_cover_errors(100, 192, 8, GRKAN_F32, p) != 0
+    assert grkan.plan_cover_errors(100, 768, 8, GRKAN_F32, p) != 0
