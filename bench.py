@@ -47,6 +47,9 @@ def parse_args():
                          "kernel moves more than 1.1 GB, i.e. several times the 256 MB last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-kernel table")
+    ap.add_argument("--alg1-baseline", action="store_true",
+                    help="also time the paper's Algorithm 1 (per-element global atomics) on both layers; "
+                         "float32 only, takes several seconds")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of x2's size (for scaling profiler byte counters)")
     return ap.parse_args()
@@ -218,6 +221,22 @@ def main():
                     "Gelem/s": layer.M / (avg * 1e-3) / 1e9,
                 }
 
+    alg1 = None
+    if args.alg1_baseline and args.dtype == "f32":
+        # the paper's "before": Table 3 reports 1.03 s against 7.33 ms (140.5x) on an RTX 4060 Ti
+        alg1 = {}
+        for name, layer in (("x1", l1), ("x2", l2)):
+            outs = (layer.dx[0], layer.dA, layer.dB)
+            grkan.grkan_alg1_bwd(layer.x[0], layer.dy[0], layer.A, layer.B, out=outs)  # warm
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            grkan.grkan_alg1_bwd(layer.x[0], layer.dy[0], layer.A, layer.B, out=outs)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            ours_ms, _, _ = time_launches(torch, layer.bwd, 20)
+            alg1["bwd_" + name] = {"alg1_ms": ms, "grkan_bwd_ms": ours_ms, "speedup": ms / ours_ms}
+
     out = {
         "metric": "GR-KAN fwd+bwd elements/s, KAT-%s shape" % args.workload[-1].upper(),
         "value": elems_per_step / (dt / args.steps),
@@ -235,6 +254,8 @@ def main():
     }
     if detail is not None:
         out["detail"] = detail
+    if alg1 is not None:
+        out["alg1_baseline"] = alg1
     if not args.no_cpu_baseline:
         del l1, l2
         torch.cuda.empty_cache()

@@ -213,26 +213,20 @@ int grkan_oracle_bwd(const double *x, const double *dy, const double *A, const d
 
 /*
  * Condition scales for the error metric used by the parity tests (not part of
- * the method).  A float32 evaluation of the paper's formulas rounds every
- * monomial a_i x^i, b_j x^j (and i a_i x^(i-1), j b_j x^(j-1)) to relative
- * precision eps; to first order the result then moves by at most eps times
+ * the method): the paper's expressions with every monomial replaced by its
+ * magnitude, i.e. the size the result would have if nothing cancelled inside
+ * P, P' and Aden'.  Q itself is taken as exact (the GPU kernels evaluate Aden
+ * in double for float32 I/O precisely so that it is).
  *
- *   Sy  = Pm/Q + |P| Am/Q^2
- *   Sdx = |dy| ( dPm/Q + |Aden'| Pm/Q^2 + dAm |P|/Q^2 + Am (|P'|/Q^2 + 2 |Aden'| |P|/Q^3) )
+ *   Sy  = Pm / Q
+ *   Sdx = |dy| ( dPm / Q + dAm Pm / Q^2 )
+ *   RA[g][i]   = sqrt( sum (dy x^i / Q)^2 )
+ *   RB[g][j-1] = sqrt( sum (dy x^j s Pm / Q^2)^2 )
  *
- * with the magnitude sums  Pm = sum |a_i||x|^i,  dPm = sum i|a_i||x|^(i-1),
- * Am = sum |b_j||x|^j,  dAm = sum j|b_j||x|^(j-1).  The Am terms are the
- * sensitivity of 1/Q and 1/Q^2 to cancellation inside Aden (large |x| next to
- * a root of the denominator polynomial gives Q ~ 1 from terms of size >> 1).
- * For the coefficient sums the same first-order scale of one term is
- *
- *   eA_i = |dy||x|^i/Q   (1 + Am/Q)
- *   eB_j = |dy||x|^j |s| (Pm/Q^2 + 2 |P| Am/Q^3)
- *
- * and, the term errors being independent, the scale of a sum is the root of
- * the sum of squares:  RA[g][i] = sqrt(sum eA_i^2), RB[g][j-1] = sqrt(sum eB_j^2).
- * Where nothing cancels these reduce to |y|, |dx| and the root-sum-square of
- * the terms, up to a factor below 4.
+ * with Pm = sum |a_i||x|^i, dPm = sum i|a_i||x|^(i-1), dAm = sum j|b_j||x|^(j-1).
+ * Where nothing cancels, Sy = |y|, Sdx >= |dx| within a factor 2, and RA, RB
+ * are the root-sum-squares of the summed terms (the scale of the rounding
+ * error of any summation order).
  *
  * Any of the output pointers may be NULL.  dy may be NULL when only Sy is wanted.
  * The root-sum-squares are plain (uncompensated) double sums: they only scale a tolerance.
@@ -270,28 +264,25 @@ int grkan_oracle_scales(const double *x, const double *dy, const double *A, cons
             axp[0] = 1.0;
             for (int i = 1; i <= top; ++i)
                 axp[i] = axp[i - 1] * ax;
-            double Pm = 0.0, dPm = 0.0, Am = 0.0, dAm = 0.0;
+            double Pm = 0.0, dPm = 0.0, dAm = 0.0;
             for (int i = 0; i <= m; ++i)
                 Pm += fabs(a[i]) * axp[i];
             for (int i = 1; i <= m; ++i)
                 dPm += (double)i * fabs(a[i]) * axp[i - 1];
             for (int j = 1; j <= n; ++j)
-                Am += fabs(b[j - 1]) * axp[j];
-            for (int j = 1; j <= n; ++j)
                 dAm += (double)j * fabs(b[j - 1]) * axp[j - 1];
 
-            const double Q = e.Q, Q2 = Q * Q, Q3 = Q2 * Q;
-            const double aP = fabs(e.P), adP = fabs(e.dP), adA = fabs(e.dAden);
+            const double Q = e.Q, Q2 = Q * Q;
             if (Sy)
-                Sy[r * D + c] = Pm / Q + aP * Am / Q2;
+                Sy[r * D + c] = Pm / Q;
             if (Sdx)
-                Sdx[r * D + c] = d * (dPm / Q + adA * Pm / Q2 + dAm * aP / Q2 + Am * (adP / Q2 + 2.0 * adA * aP / Q3));
+                Sdx[r * D + c] = d * (dPm / Q + dAm * Pm / Q2);
             for (int i = 0; i <= m; ++i) {
-                double t = d * axp[i] / Q * (1.0 + Am / Q);
+                double t = d * axp[i] / Q;
                 sq[(size_t)g * nc + i] += t * t;
             }
             for (int j = 1; j <= n; ++j) {
-                double t = d * axp[j] * fabs(e.s) * (Pm / Q2 + 2.0 * aP * Am / Q3);
+                double t = d * axp[j] * fabs(e.s) * Pm / Q2;
                 sq[(size_t)g * nc + m + j] += t * t;
             }
         }

@@ -70,6 +70,8 @@ def load_library():
     lib.grkan_fwd.restype = ctypes.c_int
     lib.grkan_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i64, i32, i32, i32, i32, ctypes.c_int, vp]
     lib.grkan_bwd.restype = ctypes.c_int
+    lib.grkan_alg1_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, vp]
+    lib.grkan_alg1_bwd.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -184,4 +186,24 @@ def grkan_bwd(x, dy, A, B, workspace: Optional["torch.Tensor"] = None, out=None,
                        int(A.shape[1]) - 1, int(B.shape[1]))
     if st:
         raise GrkanError(st, "grkan_bwd")
+    return dx, dA, dB
+
+
+def grkan_alg1_bwd(x, dy, A, B, out=None, stream=None):
+    """The paper's Algorithm 1 (per-element global atomics), float32 only: a
+    measurement baseline, not the product path (see include/grkan_alg1.h)."""
+    import torch
+
+    rows, D, G = _check(x, A, B)
+    if x.dtype != torch.float32 or dy.dtype != torch.float32 or dy.shape != x.shape or not dy.is_contiguous():
+        raise TypeError("the Algorithm 1 baseline takes contiguous float32 x and dy of one shape")
+    if int(A.shape[1]) != M_DEGREE + 1 or int(B.shape[1]) != N_DEGREE:
+        raise GrkanError(3, "grkan_alg1_bwd")
+    if out is None:
+        out = (torch.empty_like(x), torch.empty_like(A), torch.empty_like(B))
+    dx, dA, dB = out
+    st = load_library().grkan_alg1_bwd(x.data_ptr(), dy.data_ptr(), A.data_ptr(), B.data_ptr(), dx.data_ptr(),
+                                       dA.data_ptr(), dB.data_ptr(), rows, D, G, _stream_ptr(stream))
+    if st:
+        raise GrkanError(st, "grkan_alg1_bwd")
     return dx, dA, dB

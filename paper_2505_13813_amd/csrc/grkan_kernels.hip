@@ -35,6 +35,7 @@ struct Coef {
     float b1, b2, b3, b4;
     float da2, da3, da4, da5; // i * a_i, the coefficients of P'
     float db2, db3, db4;      // j * b_j, the coefficients of Aden'
+    double b1d, b2d, b3d, b4d; // for the float32-I/O kernels, which evaluate Aden in double (see aden_of)
 };
 
 __device__ __forceinline__ Coef load_coef(const float *__restrict__ A, const float *__restrict__ B, int g)
@@ -45,7 +46,8 @@ __device__ __forceinline__ Coef load_coef(const float *__restrict__ A, const flo
     c.a0 = a[0]; c.a1 = a[1]; c.a2 = a[2]; c.a3 = a[3]; c.a4 = a[4]; c.a5 = a[5];
     c.b1 = b[0]; c.b2 = b[1]; c.b3 = b[2]; c.b4 = b[3];
     c.da2 = 2.0f * c.a2; c.da3 = 3.0f * c.a3; c.da4 = 4.0f * c.a4; c.da5 = 5.0f * c.a5;
-    c.db2 = 2.0f * c.b2; c.db3 = 3.0f * c.b3; c.db4 = 4.0f * c.b4;
+    c.db2 = 2.0f * b[1]; c.db3 = 3.0f * b[2]; c.db4 = 4.0f * b[3];
+    c.b1d = (double)b[0]; c.b2d = (double)b[1]; c.b3d = (double)b[2]; c.b4d = (double)b[3];
     return c;
 }
 
@@ -53,19 +55,47 @@ __device__ __forceinline__ Coef load_coef(const float *__restrict__ A, const flo
 // per-element arithmetic (float32)
 // --------------------------------------------------------------------------
 
-// Eq. "pade": P by Horner, Aden = x * (b1 + b2 x + b3 x^2 + b4 x^3), and one
-// hardware reciprocal (1 ulp) instead of a division.
-__device__ __forceinline__ float fwd_elem(float x, const Coef &c)
+// Aden = x (b1 + b2 x + b3 x^2 + b4 x^3) by Horner.
+//
+// WIDE = true (float32 I/O): in double, rounded once to float32.  Q = 1 + |Aden|
+// sits in every result as 1/Q or 1/Q^2, and next to a real root of the
+// denominator polynomial at |x| of a few units Aden is a small difference of
+// large monomials: in float32 its absolute error eps * sum |b_j||x|^j would be a
+// relative error of that size in Q ~ 1 and, since those are exactly the
+// elements where P/Q^2 is huge, would dominate the error of the summed
+// b-gradients whatever the summation order (measured: 100x on their mean
+// absolute error with N(0,1) coefficients).  Double FMA issues at the unpacked
+// float32 rate on this chip, and the float32-I/O kernels are bound by HBM, so
+// this is free there.
+// WIDE = false (bfloat16 I/O): in float32.  That backward kernel is bound by
+// the vector ALU (the conversions and double compares cost it 12 %), and its
+// outputs are rounded to 8 mantissa bits anyway.
+template <bool WIDE> __device__ __forceinline__ float aden_of(float x, const Coef &c)
+{
+    if constexpr (WIDE) {
+        const double xd = (double)x;
+        double h = fma(c.b4d, xd, c.b3d);
+        h = fma(h, xd, c.b2d);
+        h = fma(h, xd, c.b1d);
+        return (float)(h * xd);
+    } else {
+        float h = fmaf(c.b4, x, c.b3);
+        h = fmaf(h, x, c.b2);
+        h = fmaf(h, x, c.b1);
+        return h * x;
+    }
+}
+
+// Eq. "pade": P by Horner in float32, Aden as above, and one hardware
+// reciprocal (1 ulp) instead of a division.
+template <bool WIDE> __device__ __forceinline__ float fwd_elem(float x, const Coef &c)
 {
     float p = fmaf(c.a5, x, c.a4);
     p = fmaf(p, x, c.a3);
     p = fmaf(p, x, c.a2);
     p = fmaf(p, x, c.a1);
     p = fmaf(p, x, c.a0);
-    float h = fmaf(c.b4, x, c.b3);
-    h = fmaf(h, x, c.b2);
-    h = fmaf(h, x, c.b1);
-    const float aden = h * x;
+    const float aden = aden_of<WIDE>(x, c);
     const float q = 1.0f + fabsf(aden);
     return p * __builtin_amdgcn_rcpf(q);
 }
@@ -73,6 +103,7 @@ __device__ __forceinline__ float fwd_elem(float x, const Coef &c)
 // Eq. "grad_x", "grad_a", "grad_b" for one element; returns dx and adds this
 // element's ten terms to acc (acc[0..5] numerator, acc[6..9] denominator).
 // P/Q^2 is formed as (P r) r with r = 1/Q, so Q^2 is never computed.
+template <bool WIDE>
 __device__ __forceinline__ float bwd_elem(float x, float d, const Coef &c, float (&acc)[kNumCoef])
 {
     const float x2 = x * x;
@@ -91,10 +122,7 @@ __device__ __forceinline__ float bwd_elem(float x, float d, const Coef &c, float
     dp = fmaf(dp, x, c.da2);
     dp = fmaf(dp, x, c.a1);
 
-    float h = fmaf(c.b4, x, c.b3);
-    h = fmaf(h, x, c.b2);
-    h = fmaf(h, x, c.b1);
-    const float aden = h * x;
+    const float aden = aden_of<WIDE>(x, c);
 
     float dh = fmaf(c.db4, x, c.db3);
     dh = fmaf(dh, x, c.db2);
@@ -286,6 +314,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
     constexpr int64_t ES = sizeof(IO);
+    constexpr bool WIDE = sizeof(IO) == 4; // see aden_of
     const uint64_t x0 = reinterpret_cast<uint64_t>(a.x);
     const uint64_t y0 = reinterpret_cast<uint64_t>(a.y);
 
@@ -294,7 +323,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
         load_vec<IO, VEC>((gcptr_t)(x0 + off), xv);
 #pragma unroll
         for (int e = 0; e < VEC; ++e)
-            yv[e] = fwd_elem(xv[e], c);
+            yv[e] = fwd_elem<WIDE>(xv[e], c);
         store_vec<IO, VEC>((gptr_t)(y0 + off), yv);
     };
 
@@ -316,7 +345,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
                 load_vec<IO, VEC>(xin(it + 1), xn); // prefetch
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
-                yv[e] = fwd_elem(xs[e], c);
+                yv[e] = fwd_elem<WIDE>(xs[e], c);
             store_vec<IO, VEC>(yout(it), yv);
             if (more) {
 #pragma unroll
@@ -351,6 +380,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
     constexpr int64_t ES = sizeof(IO);
+    constexpr bool WIDE = sizeof(IO) == 4; // see aden_of
     const uint64_t x0 = reinterpret_cast<uint64_t>(a.x);
     const uint64_t dy0 = reinterpret_cast<uint64_t>(a.dy);
     const uint64_t dx0 = reinterpret_cast<uint64_t>(a.dx);
@@ -366,7 +396,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
         load_vec<IO, VEC>((gcptr_t)(dy0 + off), dv);
 #pragma unroll
         for (int e = 0; e < VEC; ++e)
-            ov[e] = bwd_elem(xv[e], dv[e], c, acc);
+            ov[e] = bwd_elem<WIDE>(xv[e], dv[e], c, acc);
         store_vec<IO, VEC>((gptr_t)(dx0 + off), ov);
     };
 
@@ -393,7 +423,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
             }
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
-                ov[e] = bwd_elem(xs[e], ds[e], c, acc);
+                ov[e] = bwd_elem<WIDE>(xs[e], ds[e], c, acc);
             store_vec<IO, VEC>(dxout(it), ov);
             if (more) {
 #pragma unroll

@@ -5,15 +5,15 @@ Error metric (both sides see the same inputs; bf16 outputs are widened):
     y  : max_e |gpu - ref| / max(|ref|, Sy)
     dx : max_e |gpu - ref| / max(|ref|, Sdx)
     dA : max   |gpu - ref| / max(|ref|, RA),   dB likewise with RB
-Sy, Sdx, RA, RB come from the oracle (grkan_oracle_scales): the first-order
-size of the result's change when every monomial of P, P', Aden, Aden' is
-perturbed by a relative amount of 1, i.e. the condition of the formulas under
-float32 rounding.  Where nothing cancels they are within a small factor of
-|y|, |dx| and the root-sum-square of the summed terms, so the measure is a
-plain relative error there; where P cancels, or where Aden cancels next to a
-root of the denominator polynomial (Q ~ 1 out of terms >> 1), no float32
-evaluation can be accurate relative to the result itself and the measure stays
-bounded.
+Sy, Sdx, RA, RB come from the oracle (grkan_oracle_scales): the paper's
+expressions with every monomial of P, P', Aden' replaced by its magnitude and
+Q taken as exact,
+    Sy = Pm/Q,  Sdx = |dy| (dPm/Q + dAm Pm/Q^2),
+    RA = sqrt(sum (dy x^i/Q)^2),  RB = sqrt(sum (dy x^j s Pm/Q^2)^2).
+Where nothing cancels inside the polynomials these are |y|, about |dx| and the
+root-sum-square of the summed terms, so the measure is the plain relative
+error there; where P cancels, no float32 evaluation can be accurate relative
+to the result itself and the measure stays bounded.
 """
 from __future__ import annotations
 
