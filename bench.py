@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--alg1-baseline", action="store_true",
                     help="also time the paper's Algorithm 1 (per-element global atomics) on both layers; "
                          "float32 only, takes several seconds")
+    ap.add_argument("--mlp-block", action="store_true",
+                    help="also time the KAT MLP block (two GR-KAN layers, torch GEMMs) against a standard "
+                         "GELU MLP block, forward+backward, at the workload's x1 shape")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of x2's size (for scaling profiler byte counters)")
     return ap.parse_args()
@@ -237,6 +240,33 @@ def main():
             ours_ms, _, _ = time_launches(torch, layer.bwd, 20)
             alg1["bwd_" + name] = {"alg1_ms": ms, "grkan_bwd_ms": ours_ms, "speedup": ms / ours_ms}
 
+    block = None
+    if args.mlp_block:
+        # context for the paper's "FlashKAT is still about 25 % slower than a standard Transformer"
+        from paper_2505_13813_amd import nn as gnn
+
+        block = {}
+        dim = l1.D
+        for dt_name, tdt in (("bf16", torch.bfloat16), ("f32", torch.float32)):
+            xb = torch.randn(cfg.batch, 197, dim, device="cuda:0", dtype=tdt, requires_grad=True)
+            gb = torch.randn(cfg.batch, 197, dim, device="cuda:0", dtype=tdt)
+            std = torch.nn.Sequential(torch.nn.Linear(dim, 4 * dim), torch.nn.GELU(), torch.nn.Linear(4 * dim, dim))
+            kat = gnn.KATMlp(dim, groups=cfg.G)
+            res = {}
+            for name, mod in (("gelu_mlp", std), ("kat_mlp", kat)):
+                mod = mod.to("cuda:0").to(tdt)
+
+                def fb(_i, mod=mod):
+                    xb.grad = None
+                    mod(xb).backward(gb)
+
+                for i in range(3):
+                    fb(i)
+                avg, med, mn = time_launches(torch, fb, 20)
+                res[name + "_ms"] = med
+            res["kat_over_gelu"] = res["kat_mlp_ms"] / res["gelu_mlp_ms"]
+            block[dt_name] = res
+
     out = {
         "metric": "GR-KAN fwd+bwd elements/s, KAT-%s shape" % args.workload[-1].upper(),
         "value": elems_per_step / (dt / args.steps),
@@ -256,6 +286,8 @@ def main():
         out["detail"] = detail
     if alg1 is not None:
         out["alg1_baseline"] = alg1
+    if block is not None:
+        out["mlp_block"] = block
     if not args.no_cpu_baseline:
         del l1, l2
         torch.cuda.empty_cache()

@@ -1,0 +1,162 @@
+"""PyTorch front end of the GR-KAN layer: an autograd function over the HIP
+kernels, the group-wise rational module with the paper's model-level
+conventions, the GR-KAN linear layer and the KAT MLP block.
+
+Only the rational function runs in this package's kernels; the matrix products
+are torch's (library GEMMs).  Conventions taken from the FlashKAT paper:
+  * GR-KAN(x) = W F(x): the rational function is applied to the INPUT of each
+    linear layer (Eq. "GR_KAN").
+  * "each of the 8 groups shares its 6 numerator coefficients and has 4 unique
+    denominator coefficients" (Sec. "Results"): one numerator row, broadcast to
+    the kernel's [G, 6] layout; autograd's expand sums dA over the groups.
+  * the first rational of an MLP block starts as the identity, the second as a
+    Swish (Sec. "Results").  The paper prints no Swish coefficients, so they
+    are obtained here by a (linearised) least-squares fit on [-3, 3].
+  * variance-preserving weights (Sec. "Kolmogorov-Arnold Transformer"):
+    W ~ N(0, alpha / d_in).  The paper prints alpha = E[F(x)^2] / Var[x], which
+    would not preserve the variance (Var[W F(x)] = d_in * Var[w] * E[F^2]); the
+    stated purpose decides, so alpha = Var[x] / E[F(x)^2] here, with
+    x ~ N(0, 1) -- the usual gain (2 for ReLU).  Both readings coincide for the
+    identity initialisation.
+"""
+from __future__ import annotations
+
+import math
+from functools import lru_cache
+from typing import Tuple
+
+import numpy as np
+import torch
+from torch import nn
+
+from . import binding
+
+M_DEGREE = binding.M_DEGREE
+N_DEGREE = binding.N_DEGREE
+
+
+class GroupRationalFunction(torch.autograd.Function):
+    """y = F(x) group-wise; backward through grkan_bwd (nothing but x, A, B is saved)."""
+
+    @staticmethod
+    def forward(ctx, x, A, B):
+        x = x.contiguous()
+        A = A.contiguous()
+        B = B.contiguous()
+        ctx.save_for_backward(x, A, B)
+        return binding.grkan_fwd(x, A, B)
+
+    @staticmethod
+    def backward(ctx, dy):
+        x, A, B = ctx.saved_tensors
+        dx, dA, dB = binding.grkan_bwd(x, dy.contiguous(), A, B)
+        return dx, dA, dB
+
+
+def group_rational(x, A, B):
+    """Functional form: x [..., D] float32/bfloat16 on the GPU, A [G, 6], B [G, 4] float32."""
+    return GroupRationalFunction.apply(x, A, B)
+
+
+def _rational_np(x, a, b):
+    p = sum(a[i] * x ** i for i in range(len(a)))
+    q = 1.0 + np.abs(sum(b[j] * x ** (j + 1) for j in range(len(b))))
+    return p / q
+
+
+@lru_cache(maxsize=None)
+def swish_coefficients() -> Tuple[Tuple[float, ...], Tuple[float, ...]]:
+    """(a_0..a_5, b_1..b_4) of a safe Pade unit fitted to Swish, x * sigmoid(x).
+
+    Linearised least squares on a uniform grid over [-3, 3]: minimise
+    |P(x) - t(x) * sum_j b_j x^j - t(x)| over (a, b), which is linear.  The
+    solution has an even, non-negative denominator polynomial
+    (b_1 = b_3 = 0, b_2, b_4 > 0), so the absolute value of the safe unit is
+    inactive and the fit error of F itself is below 1e-6 on the grid (8e-3 on
+    [-6, 6]).  Deterministic: plain linear algebra in float64.
+    """
+    xs = np.linspace(-3.0, 3.0, 601)
+    target = xs / (1.0 + np.exp(-xs))
+    cols = [xs ** i for i in range(M_DEGREE + 1)] + [-target * xs ** (j + 1) for j in range(N_DEGREE)]
+    theta, *_ = np.linalg.lstsq(np.stack(cols, axis=1), target, rcond=None)
+    return tuple(float(v) for v in theta[:M_DEGREE + 1]), tuple(float(v) for v in theta[M_DEGREE + 1:])
+
+
+def second_moment(a, b, points: int = 128) -> float:
+    """E[F(x)^2] for x ~ N(0, 1) by Gauss-Hermite quadrature."""
+    t, w = np.polynomial.hermite_e.hermegauss(points)
+    f = _rational_np(t, np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64))
+    return float(np.sum(w * f * f) / math.sqrt(2.0 * math.pi))
+
+
+class GroupRational(nn.Module):
+    """The group-wise rational function with learnable coefficients.
+
+    `init`: "identity" (a = e_1, b = 0) or "swish".  With `shared_numerator`
+    (the paper's setting) there is one numerator row for all groups.
+    """
+
+    def __init__(self, groups: int = 8, init: str = "identity", shared_numerator: bool = True):
+        super().__init__()
+        if init == "identity":
+            a = [0.0, 1.0] + [0.0] * (M_DEGREE - 1)
+            b = [0.0] * N_DEGREE
+        elif init == "swish":
+            a, b = swish_coefficients()
+        else:
+            raise ValueError("init must be 'identity' or 'swish'")
+        self.groups = int(groups)
+        self.shared_numerator = bool(shared_numerator)
+        a_t = torch.tensor(a, dtype=torch.float32)
+        b_t = torch.tensor(b, dtype=torch.float32)
+        self.numerator = nn.Parameter(a_t.clone() if shared_numerator else a_t.repeat(self.groups, 1))
+        self.denominator = nn.Parameter(b_t.repeat(self.groups, 1))
+
+    def coefficient_rows(self):
+        A = self.numerator.expand(self.groups, M_DEGREE + 1) if self.shared_numerator else self.numerator
+        return A, self.denominator
+
+    def second_moment(self) -> float:
+        """E[F(x)^2], x ~ N(0,1), averaged over the groups (they start identical)."""
+        A, B = self.coefficient_rows()
+        A = A.detach().cpu().numpy()
+        B = B.detach().cpu().numpy()
+        return float(np.mean([second_moment(A[g], B[g]) for g in range(self.groups)]))
+
+    def forward(self, x):
+        A, B = self.coefficient_rows()
+        return group_rational(x, A.to(torch.float32), B.to(torch.float32))
+
+
+class GRKANLinear(nn.Module):
+    """GR-KAN(x) = W F(x) + bias (Eq. "GR_KAN"), variance-preserving init."""
+
+    def __init__(self, in_features: int, out_features: int, groups: int = 8, init: str = "identity",
+                 bias: bool = True, shared_numerator: bool = True):
+        super().__init__()
+        if in_features % groups:
+            raise ValueError("in_features must be a multiple of groups")
+        self.rational = GroupRational(groups, init, shared_numerator)
+        self.linear = nn.Linear(in_features, out_features, bias=bias)
+        alpha = 1.0 / self.rational.second_moment()  # Var[x] / E[F(x)^2] with Var[x] = 1
+        with torch.no_grad():
+            self.linear.weight.normal_(0.0, math.sqrt(alpha / in_features))
+            if bias:
+                self.linear.bias.zero_()
+
+    def forward(self, x):
+        return self.linear(self.rational(x))
+
+
+class KATMlp(nn.Module):
+    """The MLP of a KAT block: two GR-KAN layers, hidden width 4x by default;
+    the first rational starts as the identity, the second as Swish."""
+
+    def __init__(self, dim: int, hidden: int | None = None, groups: int = 8):
+        super().__init__()
+        hidden = 4 * dim if hidden is None else hidden
+        self.fc1 = GRKANLinear(dim, hidden, groups, init="identity")
+        self.fc2 = GRKANLinear(hidden, dim, groups, init="swish")
+
+    def forward(self, x):
+        return self.fc2(self.fc1(x))
