@@ -101,7 +101,8 @@ template <bool WIDE> __device__ __forceinline__ float fwd_elem(float x, const Co
 }
 
 // Eq. "grad_x", "grad_a", "grad_b" for one element; returns dx and adds this
-// element's ten terms to acc (acc[0..5] numerator, acc[6..9] denominator).
+// element's ten terms to acc (acc[0..5] numerator, acc[6..9] denominator, the
+// latter with the opposite sign until negate_b_sums is applied).
 // P/Q^2 is formed as (P r) r with r = 1/Q, so Q^2 is never computed.
 template <bool WIDE>
 __device__ __forceinline__ float bwd_elem(float x, float d, const Coef &c, float (&acc)[kNumCoef])
@@ -139,15 +140,18 @@ __device__ __forceinline__ float bwd_elem(float x, float d, const Coef &c, float
     acc[4] = fmaf(t, x4, acc[4]);
     acc[5] = fmaf(t, x5, acc[5]);
 
-    const float z0 = (p * r) * r;                                        // P / Q^2
-    const float z = aden > 0.0f ? z0 : (aden < 0.0f ? -z0 : 0.0f);       // sign(Aden) P / Q^2, sign(0) = 0
-    const float dx = d * fmaf(dp, r, -(dh * z));
-
-    const float wb = -(d * z);
+    // s / Q with s = sign(Aden), sign(0) = 0: r > 0, so the sign is copied onto it bitwise
+    const float sr = aden != 0.0f ? __builtin_copysignf(r, aden) : 0.0f;
+    // acc[6..9] collect +dy s P x^j / Q^2; the minus sign of Eq. "grad_b" is
+    // applied once per lane after the loop (negate_b_sums)
+    const float wb = d * ((p * r) * sr); // dy s P / Q^2
     acc[6] = fmaf(wb, x, acc[6]);
     acc[7] = fmaf(wb, x2, acc[7]);
     acc[8] = fmaf(wb, x3, acc[8]);
     acc[9] = fmaf(wb, x4, acc[9]);
+
+    // dx = dy (P'/Q - s Aden' P/Q^2) = (dy/Q) P' - (dy s P/Q^2) Aden'
+    const float dx = fmaf(t, dp, -(wb * dh));
     return dx;
 }
 
@@ -165,6 +169,13 @@ __device__ __forceinline__ uint64_t uniform_u64(uint64_t v)
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
     return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ void negate_b_sums(float (&acc)[kNumCoef])
+{
+#pragma unroll
+    for (int k = 6; k < kNumCoef; ++k)
+        acc[k] = -acc[k];
 }
 
 // --------------------------------------------------------------------------
@@ -193,11 +204,20 @@ template <int BYTES> __device__ __forceinline__ uint32_t raw_word(const typename
         return (uint32_t)r;
 }
 
-template <typename IO, int VEC> __device__ __forceinline__ void load_vec(gcptr_t p, float (&out)[VEC])
+// A lane's vector as it sits in memory (raw bits), so that a prefetched vector
+// can sit in registers untouched while the wave works on the current one:
+// converting at load time would make the wave wait for the data immediately.
+template <typename IO, int VEC> using RawT = typename RawOf<(int)sizeof(IO) * VEC>::type;
+
+template <typename IO, int VEC> __device__ __forceinline__ RawT<IO, VEC> load_raw(gcptr_t p)
+{
+    using Raw = RawT<IO, VEC>;
+    return __builtin_nontemporal_load((const __attribute__((address_space(1))) Raw *)p);
+}
+
+template <typename IO, int VEC> __device__ __forceinline__ void unpack(const RawT<IO, VEC> &r, float (&out)[VEC])
 {
     constexpr int BYTES = (int)sizeof(IO) * VEC;
-    using Raw = typename RawOf<BYTES>::type;
-    const Raw r = __builtin_nontemporal_load((const __attribute__((address_space(1))) Raw *)p);
     if constexpr (sizeof(IO) == 4) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i)
@@ -213,6 +233,11 @@ template <typename IO, int VEC> __device__ __forceinline__ void load_vec(gcptr_t
             out[2 * i + 1] = __builtin_bit_cast(float, w & 0xffff0000u);
         }
     }
+}
+
+template <typename IO, int VEC> __device__ __forceinline__ void load_vec(gcptr_t p, float (&out)[VEC])
+{
+    unpack<IO, VEC>(load_raw<IO, VEC>(p), out);
 }
 
 template <typename IO, int VEC> __device__ __forceinline__ void store_vec(gptr_t p, const float (&in)[VEC])
@@ -340,18 +365,16 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
             load_vec<IO, VEC>(xin(0), xs);
         for (int32_t it = 0; it < n_it; ++it) {
             const bool more = it + 1 < n_it;
-            float xn[VEC], yv[VEC];
+            RawT<IO, VEC> xn{};
             if (more)
-                load_vec<IO, VEC>(xin(it + 1), xn); // prefetch
+                xn = load_raw<IO, VEC>(xin(it + 1)); // prefetch: raw, untouched until after the arithmetic
+            float yv[VEC];
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
                 yv[e] = fwd_elem<WIDE>(xs[e], c);
             store_vec<IO, VEC>(yout(it), yv);
-            if (more) {
-#pragma unroll
-                for (int e = 0; e < VEC; ++e)
-                    xs[e] = xn[e];
-            }
+            if (more)
+                unpack<IO, VEC>(xn, xs); // the wait for the prefetch lands here
         }
         if (tail)
             one(base0 + (uint64_t)(uint32_t)n_it * step + lo);
@@ -416,21 +439,19 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
         }
         for (int32_t it = 0; it < n_it; ++it) {
             const bool more = it + 1 < n_it;
-            float xn[VEC], dn[VEC], ov[VEC];
-            if (more) { // prefetch the next chunk before working on this one
-                load_vec<IO, VEC>(xin(it + 1), xn);
-                load_vec<IO, VEC>(dyin(it + 1), dn);
+            RawT<IO, VEC> xn{}, dn{};
+            if (more) { // prefetch the next chunk: raw, untouched until after the arithmetic
+                xn = load_raw<IO, VEC>(xin(it + 1));
+                dn = load_raw<IO, VEC>(dyin(it + 1));
             }
+            float ov[VEC];
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
                 ov[e] = bwd_elem<WIDE>(xs[e], ds[e], c, acc);
             store_vec<IO, VEC>(dxout(it), ov);
-            if (more) {
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    xs[e] = xn[e];
-                    ds[e] = dn[e];
-                }
+            if (more) { // the wait for the prefetch lands here
+                unpack<IO, VEC>(xn, xs);
+                unpack<IO, VEC>(dn, ds);
             }
         }
         if (tail)
@@ -445,6 +466,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
             one((uint64_t)(elem_offset(p, id.g, s) * ES));
     }
 
+    negate_b_sums(acc);
     if constexpr (!LANECOEF) {
         // registers -> wavefront (DPP) -> workgroup (LDS) -> one workspace row per group
         __shared__ float wave_part[kWavesPerWg][kNumCoef];
