@@ -53,9 +53,11 @@ def load_library():
     if _lib is not None:
         return _lib
     if not LIB_PATH.exists():
-        raise RuntimeError(
-            "%s is missing: build it with `python -m paper_2505_13813_amd.build` "
-            "(there is no fallback path)" % LIB_PATH)
+        # nothing built yet: build once (hipcc cross-compiles without a GPU).  There is no
+        # fallback path: if this fails, loading fails.
+        from . import build as _build
+
+        _build.build_library(force=True)
     lib = ctypes.CDLL(str(LIB_PATH))
     vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
     lib.grkan_status_string.argtypes = [ctypes.c_int]

@@ -259,3 +259,66 @@ def test_full_size_configuration(oracle, threads, config, tensor, dtype, G):
     well = np.abs(dA) > 10 * RA
     if well.any():
         assert np.max(np.abs(gpu["dA"] - dA)[well] / np.abs(dA)[well]) <= TOL[dtype]["dA"]
+
+
+# ------------------------------------------------------------------ non-finite values, streams, layout
+def test_nan_propagates_only_where_it_must(oracle):
+    """IEEE propagation, no clamping: a NaN input poisons its own y and dx and
+    the coefficient sums of its own group, and nothing else."""
+    case = custom_case(11, 64, 192, 8)
+    case["x"][5, 30] = np.nan      # channel 30 -> group 1
+    gpu = run_gpu(case)
+    assert np.isnan(gpu["y"][5, 30]) and np.isnan(gpu["dx"][5, 30])
+    mask = np.ones_like(gpu["y"], dtype=bool)
+    mask[5, 30] = False
+    assert np.all(np.isfinite(gpu["y"][mask])) and np.all(np.isfinite(gpu["dx"][mask]))
+    assert np.all(np.isnan(gpu["dA"][1])) and np.all(np.isnan(gpu["dB"][1]))
+    others = [0, 2, 3, 4, 5, 6, 7]
+    clean = dict(case)
+    clean["x"] = case["x"].copy()
+    clean["x"][5, 30] = 0.25
+    ref = run_oracle(oracle, clean)
+    eA = np.abs(gpu["dA"][others] - ref["dA"][others]) / np.maximum(np.abs(ref["dA"][others]), ref["RA"][others])
+    eB = np.abs(gpu["dB"][others] - ref["dB"][others]) / np.maximum(np.abs(ref["dB"][others]), ref["RB"][others])
+    assert eA.max() <= TOL["f32"]["dA"] and eB.max() <= TOL["f32"]["dB"]
+    ey = np.abs(gpu["y"][mask] - ref["y"][mask]) / np.maximum(np.abs(ref["y"][mask]), ref["Sy"][mask])
+    assert ey.max() <= TOL["f32"]["y"]
+
+
+def test_work_is_enqueued_on_the_callers_stream(oracle):
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    case = custom_case(12, 500, 768, 8)
+    dev = to_device(case)
+    ref = run_oracle(oracle, case, threads=4)
+    side = torch.cuda.Stream()
+    x_late = torch.empty_like(dev["x"])
+    with torch.cuda.stream(side):
+        # the input is produced on the side stream just before the calls: results are right only
+        # if the kernels really run on that stream, after the copy
+        x_late.copy_(dev["x"], non_blocking=True)
+        y = grkan.grkan_fwd(x_late, dev["A"], dev["B"])
+        dx, dA, dB = grkan.grkan_bwd(x_late, dev["dy"], dev["A"], dev["B"])
+    side.synchronize()
+    gpu = dict(y=to_host(y), dx=to_host(dx), dA=to_host(dA), dB=to_host(dB))
+    assert_parity(gpu, ref, "f32", label="side stream")
+
+
+def test_binding_rejects_non_contiguous_and_mismatched_tensors():
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    x = torch.zeros(8, 384, device="cuda:0")
+    A = torch.zeros(8, 6, device="cuda:0")
+    B = torch.zeros(8, 4, device="cuda:0")
+    with pytest.raises(ValueError):
+        grkan.grkan_fwd(x[:, ::2], A, B)
+    with pytest.raises(ValueError):
+        grkan.grkan_bwd(x, x[:4], A, B)
+    with pytest.raises(TypeError):
+        grkan.grkan_fwd(x.double(), A, B)
+    with pytest.raises(TypeError):
+        grkan.grkan_fwd(x, A.double(), B)
