@@ -47,6 +47,8 @@ def parse_args():
                          "kernel moves more than 1.1 GB, i.e. several times the 256 MB last-level cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-kernel table")
+    ap.add_argument("--no-paper-micro", action="store_true",
+                    help="skip the paper's kernel micro-benchmark shape [1024,197,768]")
     ap.add_argument("--alg1-baseline", action="store_true",
                     help="also time the paper's Algorithm 1 (per-element global atomics) on both layers; "
                          "float32 only, takes several seconds")
@@ -224,6 +226,34 @@ def main():
                     "Gelem/s": layer.M / (avg * 1e-3) / 1e9,
                 }
 
+    paper_micro = None
+    if not args.no_paper_micro and args.dtype == "f32":
+        # The paper's own kernel benchmark (Sec. "Insight 2" / Table 2 and Table 3): X, dO of shape
+        # [1024, 197, 768], 8 groups; it reports 4.89 ms forward (KAT CUDA kernel) and 7.33 ms backward
+        # (FlashKAT, Triton; 1.03 s with the atomics) on an RTX 4060 Ti.  Seeded N(0,1) inputs drawn on the GPU.
+        rows_p, D_p, G_p = 1024 * 197, 768, 8
+        gen = torch.Generator(device="cuda:0").manual_seed(1000)
+        A_p = (torch.rand(G_p, 6, device="cuda:0", generator=gen) * 2 - 1) / torch.arange(1, 7, device="cuda:0")
+        B_p = torch.rand(G_p, 4, device="cuda:0", generator=gen) - 0.5
+        xs = [torch.randn(rows_p, D_p, device="cuda:0", generator=gen) for _ in range(2)]
+        dys = [torch.randn(rows_p, D_p, device="cuda:0", generator=gen) for _ in range(2)]
+        outs = [torch.empty(rows_p, D_p, device="cuda:0") for _ in range(2)]
+        dA_p, dB_p = torch.empty_like(A_p), torch.empty_like(B_p)
+        ws_p = torch.empty(grkan.grkan_bwd_workspace_bytes(rows_p, D_p, G_p, grkan.GRKAN_F32), dtype=torch.uint8,
+                           device="cuda:0")
+        f_avg, _, _ = time_launches(torch, lambda i: grkan.grkan_fwd(xs[i % 2], A_p, B_p, out=outs[i % 2]), 30)
+        b_avg, _, _ = time_launches(
+            torch, lambda i: grkan.grkan_bwd(xs[i % 2], dys[i % 2], A_p, B_p, workspace=ws_p,
+                                             out=(outs[i % 2], dA_p, dB_p)), 30)
+        m_p = rows_p * D_p
+        paper_micro = {
+            "shape": [1024, 197, 768], "G": G_p, "elements": m_p,
+            "fwd_ms": f_avg, "fwd_GBs": 8 * m_p / (f_avg * 1e-3) / 1e9,
+            "bwd_ms": b_avg, "bwd_GBs": 12 * m_p / (b_avg * 1e-3) / 1e9,
+            "paper": {"hardware": "RTX 4060 Ti", "fwd_ms": 4.89, "bwd_flashkat_ms": 7.33, "bwd_kat_atomics_ms": 1030.0},
+        }
+        del xs, dys, outs
+
     alg1 = None
     if args.alg1_baseline and args.dtype == "f32":
         # the paper's "before": Table 3 reports 1.03 s against 7.33 ms (140.5x) on an RTX 4060 Ti
@@ -268,7 +298,8 @@ def main():
             block[dt_name] = res
 
     out = {
-        "metric": "GR-KAN fwd+bwd elements/s, KAT-%s shape" % args.workload[-1].upper(),
+        "metric": "GR-KAN fwd+bwd elements/s and achieved HBM GB/s (% of peak), KAT-"
+                  + args.workload[-1].upper() + " shape",
         "value": elems_per_step / (dt / args.steps),
         "unit": "elements/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -279,11 +310,15 @@ def main():
                         % (args.workload, cfg.batch, l1.D, cfg.batch, l2.D, cfg.G),
             "elements_per_step": elems_per_step, "buffer_sets": {"x1": l1.sets, "x2": l2.sets},
             "hbm_GBs_whole_step": (l1.fwd_bytes() + l1.bwd_bytes() + l2.fwd_bytes() + l2.bwd_bytes()) / (dt / args.steps) / 1e9,
+            "hbm_frac_of_peak_whole_step": (l1.fwd_bytes() + l1.bwd_bytes() + l2.fwd_bytes() + l2.bwd_bytes())
+                                           / (dt / args.steps) / 1e9 / HBM_PEAK_GBS,
         },
         "roofline": roofline,
     }
     if detail is not None:
         out["detail"] = detail
+    if paper_micro is not None:
+        out["paper_micro_benchmark"] = paper_micro
     if alg1 is not None:
         out["alg1_baseline"] = alg1
     if block is not None:

@@ -67,8 +67,9 @@ const char *grkan_status_string(grkan_status_t status);
  * and walks that group's [rows x d_g] slab in chunks of 64 vectors;
  * `wg_per_bundle * waves_per_group_in_wg` wavefronts share a group, and a
  * workgroup holds `groups_per_wg` adjacent groups.  Flat walk (lane_coef = 1),
- * chosen when a group's row segment is shorter than 384 bytes or not a whole
- * number of 128-byte lines: wavefronts walk whole rows (the plan is that of a
+ * chosen by the forward pass always and by the backward pass when a group's
+ * row segment is shorter than 384 bytes or not a whole number of 128-byte
+ * lines: wavefronts walk whole rows (the plan is that of a
  * single group of D channels) and every lane keeps the coefficients of the
  * group its fixed column belongs to.
  */
@@ -90,11 +91,12 @@ typedef struct {
  * Pure host function: the plan for a shape on a device with `num_cu` compute
  * units that keeps `wg_per_cu` workgroups of this kernel resident per unit.
  * `align_bytes` is the largest power of two (<= 16) that divides every tensor
- * pointer.  Returns GRKAN_OK or the argument error.
+ * pointer.  `forward` != 0 plans the forward pass (which prefers the flat walk
+ * for every shape), 0 the backward pass.  Returns GRKAN_OK or the argument error.
  */
 grkan_status_t grkan_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io,
                           int32_t align_bytes, int32_t num_cu, int32_t wg_per_cu,
-                          grkan_plan_t *plan);
+                          int32_t forward, grkan_plan_t *plan);
 
 /*
  * Pure host function used by the tests: walks the plan exactly as the kernels

@@ -62,7 +62,7 @@ def load_library():
     vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
     lib.grkan_status_string.argtypes = [ctypes.c_int]
     lib.grkan_status_string.restype = ctypes.c_char_p
-    lib.grkan_plan.argtypes = [i64, i32, i32, ctypes.c_int, i32, i32, i32, ctypes.POINTER(Plan)]
+    lib.grkan_plan.argtypes = [i64, i32, i32, ctypes.c_int, i32, i32, i32, i32, ctypes.POINTER(Plan)]
     lib.grkan_plan.restype = ctypes.c_int
     lib.grkan_plan_cover_errors.argtypes = [i64, i32, i32, ctypes.c_int, ctypes.POINTER(Plan)]
     lib.grkan_plan_cover_errors.restype = i64
@@ -83,10 +83,12 @@ def status_string(status: int) -> str:
 
 
 def plan(rows: int, D: int, G: int, io: int = GRKAN_F32, align_bytes: int = 16,
-         num_cu: int = 256, wg_per_cu: int = 4) -> Plan:
-    """Host-only: the launch geometry for a shape (see grkan_plan in grkan.h)."""
+         num_cu: int = 256, wg_per_cu: int = 4, forward: bool = False) -> Plan:
+    """Host-only: the launch geometry of the backward (default) or forward pass
+    for a shape (see grkan_plan in grkan.h)."""
     p = Plan()
-    st = load_library().grkan_plan(rows, D, G, io, align_bytes, num_cu, wg_per_cu, ctypes.byref(p))
+    st = load_library().grkan_plan(rows, D, G, io, align_bytes, num_cu, wg_per_cu, 1 if forward else 0,
+                                   ctypes.byref(p))
     if st:
         raise GrkanError(st, "grkan_plan")
     return p

@@ -724,18 +724,18 @@ static Want bwd_want(grkan_dtype_t io)
 // the selected kernel can keep resident and re-plans if needed.
 template <typename Select>
 static grkan_status_t plan_resident(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, int32_t align,
-                                    const DeviceInfo &info, int dev, Want want, Select select,
+                                    const DeviceInfo &info, int dev, Want want, bool forward, Select select,
                                     grkan_plan_t *pl, Walk *walk, const void **kernel)
 {
     int per_cu = want.group_walk;
-    grkan_status_t st = make_plan(rows, D, G, io, align, info.num_cu, per_cu, pl, walk);
+    grkan_status_t st = make_plan(rows, D, G, io, align, info.num_cu, per_cu, forward, pl, walk);
     if (st != GRKAN_OK)
         return st;
     if (pl->lane_coef && want.flat_walk != per_cu) {
         grkan_plan_t alt;
-        if (make_plan(rows, D, G, io, align, info.num_cu, want.flat_walk, &alt, nullptr) == GRKAN_OK && alt.lane_coef) {
+        if (make_plan(rows, D, G, io, align, info.num_cu, want.flat_walk, forward, &alt, nullptr) == GRKAN_OK && alt.lane_coef) {
             per_cu = want.flat_walk;
-            st = make_plan(rows, D, G, io, align, info.num_cu, per_cu, pl, walk);
+            st = make_plan(rows, D, G, io, align, info.num_cu, per_cu, forward, pl, walk);
             if (st != GRKAN_OK)
                 return st;
         }
@@ -748,7 +748,7 @@ static grkan_status_t plan_resident(int64_t rows, int32_t D, int32_t G, grkan_dt
         return GRKAN_ERR_LAUNCH;
     if (fit < per_cu) {
         const int32_t was_flat = pl->lane_coef;
-        st = make_plan(rows, D, G, io, align, info.num_cu, fit, pl, walk);
+        st = make_plan(rows, D, G, io, align, info.num_cu, fit, forward, pl, walk);
         if (st != GRKAN_OK)
             return st;
         *kernel = reinterpret_cast<const void *>(select(io, pl->vec, pl->fixed_col != 0, pl->lane_coef != 0));
@@ -786,7 +786,7 @@ extern "C" size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, 
     for (int align = elem_size(io); align <= 16; align *= 2) {
         grkan_plan_t pl;
         const void *kernel = nullptr;
-        if (plan_resident(rows, D, G, io, align, info, dev, bwd_want(io), select_bwd, &pl, nullptr, &kernel) !=
+        if (plan_resident(rows, D, G, io, align, info, dev, bwd_want(io), false, select_bwd, &pl, nullptr, &kernel) !=
             GRKAN_OK)
             return 0;
         const size_t b = workspace_for(pl, G);
@@ -818,7 +818,7 @@ extern "C" grkan_status_t grkan_fwd(const void *x, const float *A, const float *
     grkan_plan_t pl;
     FwdArgs a;
     const void *kernel = nullptr;
-    st = plan_resident(rows, D, G, io, common_alignment({x, y}), info, dev, fwd_want(io), select_fwd, &pl,
+    st = plan_resident(rows, D, G, io, common_alignment({x, y}), info, dev, fwd_want(io), true, select_fwd, &pl,
                        &a.walk, &kernel);
     if (st != GRKAN_OK)
         return st;
@@ -857,7 +857,7 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
     grkan_plan_t pl;
     BwdArgs a;
     const void *kernel = nullptr;
-    st = plan_resident(rows, D, G, io, common_alignment({x, dy, dx}), info, dev, bwd_want(io), select_bwd, &pl,
+    st = plan_resident(rows, D, G, io, common_alignment({x, dy, dx}), info, dev, bwd_want(io), false, select_bwd, &pl,
                        &a.walk, &kernel);
     if (st != GRKAN_OK)
         return st;

@@ -16,7 +16,7 @@ grkan_status_t check_shape(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io)
 
 // Fills the public plan and (optionally) the kernel-side walk parameters.
 grkan_status_t make_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, int32_t align_bytes,
-                         int32_t num_cu, int32_t wg_per_cu, grkan_plan_t *out, Walk *walk);
+                         int32_t num_cu, int32_t wg_per_cu, bool forward, grkan_plan_t *out, Walk *walk);
 
 // Rebuilds the walk parameters from a public plan (validating it).
 grkan_status_t walk_from_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io,

@@ -23,8 +23,9 @@ SHAPES = [
 @pytest.mark.parametrize("io", [GRKAN_F32, GRKAN_BF16])
 def test_walk_covers_every_vector_exactly_once(rows, D, G, io):
     es = 4 if io == GRKAN_F32 else 2
-    for align, (num_cu, wg_per_cu) in itertools.product((16, 8, es), ((256, 4), (256, 8), (3, 1))):
-        p = grkan.plan(rows, D, G, io, align_bytes=align, num_cu=num_cu, wg_per_cu=wg_per_cu)
+    for align, (num_cu, wg_per_cu), forward in itertools.product((16, 8, es), ((256, 4), (256, 8), (3, 1)),
+                                                                (False, True)):
+        p = grkan.plan(rows, D, G, io, align_bytes=align, num_cu=num_cu, wg_per_cu=wg_per_cu, forward=forward)
         walk_groups = 1 if p.lane_coef else G
         assert p.grid == (walk_groups // p.groups_per_wg) * p.wg_per_bundle
         assert not p.lane_coef or p.fixed_col
@@ -69,6 +70,9 @@ def test_headline_plans():
     # stress, one group
     p = grkan.plan(50432, 3072, 1, GRKAN_F32)
     assert p.groups_per_wg == 1 and p.fixed_col == 1
+    # the forward pass walks whole rows whatever the segment length
+    p = grkan.plan(25216, 3072, 8, GRKAN_F32, forward=True)
+    assert (p.lane_coef, p.fixed_col, p.vecs_per_segment) == (1, 1, 768)
 
 
 def test_plan_is_deterministic():
