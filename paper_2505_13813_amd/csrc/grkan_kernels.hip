@@ -6,15 +6,20 @@
 // coefficient gradients per thread block and then issues one atomic add per
 // block; here there are no atomics at all:
 //
-//   stage 1  one wavefront = one group.  Each lane streams 128-bit vectors of
-//            x and dy, writes dx, and keeps the ten partial sums in registers;
-//            the wavefront then folds them with DPP row/bank operations, the
-//            workgroup folds its wavefronts through LDS, and one row of ten
-//            floats per (workgroup, group) goes to a workspace.
-//   stage 2  one workgroup per group adds that group's workspace rows in a
+//   stage 1  Each lane streams 128-bit vectors of x and dy, writes dx, and
+//            keeps the ten partial sums in registers for the whole kernel.
+//            Group walk (long, line-aligned group segments): one wavefront =
+//            one group, coefficients in scalar registers; the wavefront folds
+//            its sums with DPP row/bank operations, the workgroup folds its
+//            wavefronts through LDS.  Flat walk (short segments): wavefronts
+//            read whole rows, each lane holds the coefficients of its fixed
+//            column's group, and the workgroup folds lanes -> runs -> groups
+//            through LDS.  Either way one row of ten floats per (workgroup,
+//            group) goes to a workspace.
+//   stage 2  one wavefront per group adds that group's workspace rows in a
 //            fixed order (in double) and overwrites dA / dB.
 //
-// Both orders are fixed by the launch geometry, which is a pure function of
+// Every order is fixed by the launch geometry, which is a pure function of
 // shape, alignment and device, so dA / dB are bit-identical from run to run.
 #include <hip/hip_runtime.h>
 
@@ -28,7 +33,8 @@
 namespace grkan {
 
 // --------------------------------------------------------------------------
-// coefficients (wave-uniform: they live in scalar registers)
+// coefficients of one group (scalar registers when the group is wave-uniform,
+// vector registers in the flat walk)
 // --------------------------------------------------------------------------
 struct Coef {
     float a0, a1, a2, a3, a4, a5;
