@@ -322,3 +322,45 @@ def test_binding_rejects_non_contiguous_and_mismatched_tensors():
         grkan.grkan_fwd(x.double(), A, B)
     with pytest.raises(TypeError):
         grkan.grkan_fwd(x, A.double(), B)
+
+
+def test_random_small_shapes_against_the_oracle(oracle):
+    """Seeded sweep over awkward shapes, dtypes and pointer offsets, so that every
+    kernel variant (vector widths 1-8, group / flat / general walks) meets the
+    oracle, not only the shapes of the paper."""
+    import random
+
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    rng = random.Random(4242)
+    for trial in range(48):
+        G = rng.choice([1, 2, 3, 4, 5, 8, 16, 33])
+        dg = rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 24, 31, 32, 48, 96, 100, 192, 384])
+        rows = rng.choice([1, 2, 3, 17, 64, 65, 127, 301, 1000])
+        dtype = rng.choice(["f32", "bf16"])
+        offset = rng.choice([0, 0, 0, 1, 2, 4])  # elements the tensors are shifted off their allocation
+        D = G * dg
+        if rows * D > 600_000:
+            rows = max(1, 600_000 // D)
+        case = custom_case(100 + trial, rows, D, G, dtype)
+        dev = to_device(case)
+        n = rows * D
+
+        def shifted(t):
+            buf = torch.empty(n + 16, dtype=t.dtype, device=t.device)
+            view = buf[offset:offset + n].view(rows, D)
+            view.copy_(t)
+            return view
+
+        x, dy = shifted(dev["x"]), shifted(dev["dy"])
+        y = shifted(torch.zeros_like(dev["x"]))
+        dx = shifted(torch.zeros_like(dev["x"]))
+        dA, dB = torch.empty_like(dev["A"]), torch.empty_like(dev["B"])
+        grkan.grkan_fwd(x, dev["A"], dev["B"], out=y)
+        grkan.grkan_bwd(x, dy, dev["A"], dev["B"], out=(dx, dA, dB))
+        torch.cuda.synchronize()
+        gpu = dict(y=to_host(y), dx=to_host(dx), dA=to_host(dA), dB=to_host(dB))
+        ref = run_oracle(oracle, case)
+        assert_parity(gpu, ref, dtype, label="trial %d: %dx%d G=%d %s +%d" % (trial, rows, D, G, dtype, offset))

@@ -104,3 +104,32 @@ def test_a_corrupted_plan_fails_the_cover_check():
     p.fixed_col = 1
     p.wg_per_bundle += 1  # 64 * waves is no longer a multiple of the segment length
     assert grkan.plan_cover_errors(100, 768, 8, GRKAN_F32, p) != 0
+
+
+def test_random_shapes_are_always_covered_exactly():
+    """Seeded sweep over awkward shapes, alignments, device sizes and both
+    passes: whatever walk the planner picks, the kernels' index arithmetic
+    must visit every vector once and stay in bounds."""
+    import random
+
+    rng = random.Random(20250513)
+    modes = set()
+    for trial in range(400):
+        G = rng.choice([1, 1, 2, 3, 4, 5, 7, 8, 8, 12, 16, 33, 64])
+        dg = rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 24, 31, 32, 48, 64, 96, 100, 128, 192, 250, 384])
+        rows = rng.choice([0, 1, 2, 3, 17, 64, 65, 127, 200, 301])
+        io = rng.choice([GRKAN_F32, GRKAN_BF16])
+        es = 4 if io == GRKAN_F32 else 2
+        align = rng.choice([a for a in (2, 4, 8, 16) if a >= es])
+        num_cu, wg = rng.choice([(256, 2), (256, 4), (256, 8), (304, 3), (8, 1), (1, 1), (64, 7)])
+        forward = rng.random() < 0.5
+        D = G * dg
+        if rows * D > 400_000:
+            rows = max(1, 400_000 // D)
+        p = grkan.plan(rows, D, G, io, align_bytes=align, num_cu=num_cu, wg_per_cu=wg, forward=forward)
+        assert grkan.plan_cover_errors(rows, D, G, io, p) == 0, (trial, rows, D, G, io, align, num_cu, wg, forward,
+                                                                   p.as_dict())
+        if rows:
+            modes.add((p.fixed_col, p.lane_coef, p.groups_per_wg > 1))
+    # the sweep reaches the fixed and general group walks, bundled groups and the flat walk
+    assert {(1, 0, False), (1, 1, False)} <= modes and any(m[2] for m in modes) and any(m[0] == 0 for m in modes)
