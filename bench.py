@@ -5,7 +5,8 @@ One "step" is one pass of the whole hot path over one batch of synthetic
 activations at the KAT-B shape (per-GPU batch 128, 197 tokens): the forward and
 the backward of both rational layers of a Transformer block,
 x1 [128,197,768] and x2 [128,197,3072], 8 groups, degrees (5,4), float32,
-in training order  fwd(x1) fwd(x2) bwd(x2) bwd(x1).
+in training order  fwd(x1) fwd(x2) bwd(x2) bwd(x1).  (--workload selects the
+other configurations; the one-tensor ones run fwd(x) bwd(x).)
 `value` = elements that went through forward+backward per second, with the
 inputs resident in HBM.  Successive steps rotate over several buffer sets per layer so
 that no launch finds its inputs in the 256 MB last-level cache.
@@ -25,6 +26,8 @@ ROOT = Path(__file__).resolve().parent
 sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: 256 CUs x 64 lanes x 2.4 GHz, unpacked float32
+BWD_VALU_SLOTS_BF16 = 49  # issue slots per element of the bf16 backward loop (counted in the ISA; rcp = 4)
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); the
@@ -40,7 +43,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="kat_b", choices=["kat_t", "kat_s", "kat_b"])
+    ap.add_argument("--workload", default="kat_b", choices=["tiny", "kat_t", "kat_s", "kat_b", "stress"])
+    ap.add_argument("--groups", type=int, default=0, help="override the number of groups (stress: 1, 8 or 64)")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--sets", type=int, default=0,
                     help="buffer sets each layer rotates over (0 = enough that one rotation of the smallest "
@@ -165,57 +169,76 @@ def main():
     torch.cuda.set_device(0)
 
     cfg = grkan_inputs.CONFIGS[args.workload]
-    cases = [grkan_inputs.make_case(args.workload, t, dtype=args.dtype) for t, _ in cfg.tensors]
-    l1, l2 = (Layer(c, args.sets, torch, grkan) for c in cases)
+    G = args.groups if args.groups > 0 else cfg.G
+    cases = [grkan_inputs.make_case(args.workload, t, G=G, dtype=args.dtype) for t, _ in cfg.tensors]
+    layers = [Layer(c, args.sets, torch, grkan) for c in cases]
+    names = [t for t, _ in cfg.tensors]
+    dom = layers[-1]  # the widest tensor: its backward pass is the dominant kernel
+    dom_name = names[-1]
 
     def step(i):
-        l1.fwd(i)
-        l2.fwd(i)
-        l2.bwd(i)
-        l1.bwd(i)
+        for layer in layers:
+            layer.fwd(i)
+        for layer in reversed(layers):
+            layer.bwd(i)
 
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
 
     # timed region: exactly `steps` steps; events bracket the dominant kernel
-    # (backward of x2) on the launch stream
+    # (backward of the widest tensor) on the launch stream
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        l1.fwd(i)
-        l2.fwd(i)
+        for layer in layers:
+            layer.fwd(i)
         ev[i][0].record()
-        l2.bwd(i)
+        dom.bwd(i)
         ev[i][1].record()
-        l1.bwd(i)
+        for layer in reversed(layers[:-1]):
+            layer.bwd(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
     ms_per_step = dt * 1e3 / args.steps
-    elems_per_step = l1.M + l2.M
-    bwd2_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
-    achieved = l2.bwd_bytes() / (bwd2_ms * 1e-3) / 1e9
-    key = "%s/%s/bwd_x2" % (args.workload, args.dtype)
-    roofline = {
-        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(key),
-        "kernel": "grkan_bwd on x2 [%d,%d] (stage 1 + stage 2), %d algorithmic bytes per launch, avg %.2f us"
-                  % (l2.rows, l2.D, l2.bwd_bytes(), bwd2_ms * 1e3),
-    }
+    elems_per_step = sum(layer.M for layer in layers)
+    step_bytes = sum(layer.fwd_bytes() + layer.bwd_bytes() for layer in layers)
+    dom_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    key = "%s/%s/bwd_%s" % (args.workload, args.dtype, dom_name)
+    what = "grkan_bwd on %s [%d,%d] (stage 1 + stage 2)" % (dom_name, dom.rows, dom.D)
+    if args.dtype == "f32":
+        achieved = dom.bwd_bytes() / (dom_ms * 1e-3) / 1e9
+        roofline = {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(key),
+            "kernel": "%s, %d algorithmic bytes per launch, avg %.2f us" % (what, dom.bwd_bytes(), dom_ms * 1e3),
+        }
+    else:
+        # bf16 I/O halves the bytes but not the arithmetic: the backward pass is bound by the vector ALU.
+        # Peak = 256 CUs x 64 lanes x 2.4 GHz, one (unpacked) float32 operation per lane and clock.
+        ops = BWD_VALU_SLOTS_BF16 * dom.M
+        achieved = ops / (dom_ms * 1e-3) / 1e12
+        roofline = {
+            "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TOPS, "unit": "T lane-op/s",
+            "frac": achieved / VALU_PEAK_TOPS, "traffic": None,
+            "kernel": "%s, %d vector-ALU issue slots per element x %d elements per launch, avg %.2f us "
+                      "(HBM side: %.0f GB/s)" % (what, BWD_VALU_SLOTS_BF16, dom.M, dom_ms * 1e3,
+                                                  dom.bwd_bytes() / (dom_ms * 1e-3) / 1e9),
+        }
 
     if args.copy_calibration:
-        # a copy of known size: reads and writes l2.M elements once each
+        # a copy of known size: reads and writes dom.M elements once each
         for i in range(3):
-            l2.y[i % l2.sets].copy_(l2.x[i % l2.sets])
+            dom.y[i % dom.sets].copy_(dom.x[i % dom.sets])
         torch.cuda.synchronize()
 
     detail = None
     if not args.no_detail:
         detail = {}
         n = 40
-        for name, layer in (("x1", l1), ("x2", l2)):
+        for name, layer in zip(names, layers):
             for pname, fn, nbytes in (("fwd", layer.fwd, layer.fwd_bytes()), ("bwd", layer.bwd, layer.bwd_bytes())):
                 for _ in range(3):
                     fn(0)
@@ -258,7 +281,7 @@ def main():
     if args.alg1_baseline and args.dtype == "f32":
         # the paper's "before": Table 3 reports 1.03 s against 7.33 ms (140.5x) on an RTX 4060 Ti
         alg1 = {}
-        for name, layer in (("x1", l1), ("x2", l2)):
+        for name, layer in zip(names, layers):
             outs = (layer.dx[0], layer.dA, layer.dB)
             grkan.grkan_alg1_bwd(layer.x[0], layer.dy[0], layer.A, layer.B, out=outs)  # warm
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -276,7 +299,7 @@ def main():
         from paper_2505_13813_amd import nn as gnn
 
         block = {}
-        dim = l1.D
+        dim = layers[0].D
         for dt_name, tdt in (("bf16", torch.bfloat16), ("f32", torch.float32)):
             xb = torch.randn(cfg.batch, 197, dim, device="cuda:0", dtype=tdt, requires_grad=True)
             gb = torch.randn(cfg.batch, 197, dim, device="cuda:0", dtype=tdt)
@@ -306,12 +329,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {
-            "workload": "%s: fwd+bwd of x1 [%d,197,%d] and x2 [%d,197,%d], G=%d, degrees (5,4)"
-                        % (args.workload, cfg.batch, l1.D, cfg.batch, l2.D, cfg.G),
-            "elements_per_step": elems_per_step, "buffer_sets": {"x1": l1.sets, "x2": l2.sets},
-            "hbm_GBs_whole_step": (l1.fwd_bytes() + l1.bwd_bytes() + l2.fwd_bytes() + l2.bwd_bytes()) / (dt / args.steps) / 1e9,
-            "hbm_frac_of_peak_whole_step": (l1.fwd_bytes() + l1.bwd_bytes() + l2.fwd_bytes() + l2.bwd_bytes())
-                                           / (dt / args.steps) / 1e9 / HBM_PEAK_GBS,
+            "workload": "%s: fwd+bwd of %s, G=%d, degrees (5,4)"
+                        % (args.workload, " and ".join("%s [%d,197,%d]" % (n, cfg.batch, l.D)
+                                                       for n, l in zip(names, layers)), G),
+            "elements_per_step": elems_per_step, "buffer_sets": {n: l.sets for n, l in zip(names, layers)},
+            "hbm_GBs_whole_step": step_bytes / (dt / args.steps) / 1e9,
+            "hbm_frac_of_peak_whole_step": step_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBS,
         },
         "roofline": roofline,
     }
@@ -324,7 +347,7 @@ def main():
     if block is not None:
         out["mlp_block"] = block
     if not args.no_cpu_baseline:
-        del l1, l2
+        del layers, dom
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(cases)
     print(json.dumps(out))

@@ -737,9 +737,12 @@ static grkan_status_t plan_resident(int64_t rows, int32_t D, int32_t G, grkan_dt
     grkan_status_t st = make_plan(rows, D, G, io, align, info.num_cu, per_cu, forward, pl, walk);
     if (st != GRKAN_OK)
         return st;
-    if (pl->lane_coef && want.flat_walk != per_cu) {
+    // a single group is walked exactly like the flat walk (whole rows, contiguous per workgroup)
+    const bool rows_walk = pl->lane_coef || G == 1;
+    if (rows_walk && want.flat_walk != per_cu) {
         grkan_plan_t alt;
-        if (make_plan(rows, D, G, io, align, info.num_cu, want.flat_walk, forward, &alt, nullptr) == GRKAN_OK && alt.lane_coef) {
+        if (make_plan(rows, D, G, io, align, info.num_cu, want.flat_walk, forward, &alt, nullptr) == GRKAN_OK &&
+            alt.lane_coef == pl->lane_coef) {
             per_cu = want.flat_walk;
             st = make_plan(rows, D, G, io, align, info.num_cu, per_cu, forward, pl, walk);
             if (st != GRKAN_OK)
