@@ -34,7 +34,7 @@ BWD_VALU_SLOTS_BF16 = 49  # issue slots per element of the bf16 backward loop (c
 # summaries are under profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/bench_kat_b_f32_hbm_traffic.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB, stage 1 + stage 2
-    "kat_b/f32/bwd_x2": 907952 * 1024,
+    "kat_b/f32/bwd_x2": 907937 * 1024,
 }
 
 
