@@ -118,6 +118,38 @@ def time_launches(torch, fn, n):
     return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
 
 
+def launch_stats(torch, fn, n):
+    """As time_launches, plus the half-width of the 95 % confidence interval of
+    the mean (normal approximation, 1.96 s / sqrt(n)), all in ms."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for i in range(n):
+        ev[i][0].record()
+        fn(i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in ev)
+    mean = sum(ts) / n
+    var = sum((t - mean) ** 2 for t in ts) / max(1, n - 1)
+    return mean, ts[n // 2], ts[0], 1.96 * (var / n) ** 0.5
+
+
+def device_report(torch, grkan):
+    """What the runtime reports about the device, and the HBM peak that
+    follows from memory clock x bus width, beside the published figure the
+    roofline divides by.  The reported memory clock is HBM3E's command clock;
+    the data strobe runs at twice that, double data rate: 4 bits per pin per
+    reported cycle (2000 MHz -> 8 Gb/s per pin)."""
+    p = torch.cuda.get_device_properties(0)
+    q = grkan.device_query()
+    return {
+        "name": p.name, "compute_units": q["compute_units"], "hbm_bytes": p.total_memory,
+        "engine_clock_MHz": q["engine_clock_khz"] / 1e3, "memory_clock_MHz": q["memory_clock_khz"] / 1e3,
+        "memory_bus_bits": q["memory_bus_bits"],
+        "hbm_peak_from_clock_x_bus_GBs": 4.0 * q["memory_clock_khz"] * 1e3 * q["memory_bus_bits"] / 8 / 1e9,
+        "published_hbm_peak_GBs": HBM_PEAK_GBS,
+    }
+
+
 def cpu_baseline(cases):
     """The fp64 oracle, as it stands, on the host cores: one forward+backward
     pass over the same arrays."""
@@ -143,10 +175,20 @@ def cpu_baseline(cases):
         if dt * threads >= 15.0 or passes >= 20:  # about 15 core-seconds of oracle work
             break
     elems = passes * sum(int(p[0].size) for p in prepared)
+    # the same oracle on one thread (the sequential definition), on a bounded slice of the widest tensor
+    x, dy, A, B = prepared[-1]
+    rows1 = max(1, min(x.shape[0], 12_000_000 // x.shape[1]))
+    t1 = time.perf_counter()
+    grkan_oracle.fwd(x[:rows1], A, B, threads=1)
+    grkan_oracle.bwd(x[:rows1], dy[:rows1], A, B, threads=1)
+    dt1 = time.perf_counter() - t1
     return {
         "value": elems / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
         "sample": "%d fwd+bwd pass(es) of the fp64 C oracle over the whole workload (%d elements in total, %.2f s wall)"
                   % (passes, elems, dt),
+        "single_thread": {"value": rows1 * x.shape[1] / dt1, "unit": "elements/s", "cores": 1,
+                          "sample": "one fwd+bwd pass over the first %d rows of the widest tensor (%d elements, %.2f s)"
+                                    % (rows1, rows1 * x.shape[1], dt1)},
     }
 
 
@@ -236,17 +278,25 @@ def main():
 
     detail = None
     if not args.no_detail:
+        # per kernel: 5 warm-ups, then 100 timed launches between HIP events (the paper's protocol),
+        # rotating over the buffer sets; then the same with one buffer set, labelled "warm" (its inputs
+        # and outputs may still sit in the 256 MB last-level cache from the launch before)
         detail = {}
-        n = 40
+        n = 100
         for name, layer in zip(names, layers):
             for pname, fn, nbytes in (("fwd", layer.fwd, layer.fwd_bytes()), ("bwd", layer.bwd, layer.bwd_bytes())):
-                for _ in range(3):
+                for i in range(5):
+                    fn(i)
+                avg, med, mn, ci = launch_stats(torch, fn, n)
+                for _ in range(5):
                     fn(0)
-                avg, med, mn = time_launches(torch, fn, n)
+                w_avg, w_med, w_mn, w_ci = launch_stats(torch, lambda _i, fn=fn: fn(0), n)
                 detail["%s_%s" % (pname, name)] = {
-                    "avg_us": avg * 1e3, "median_us": med * 1e3, "min_us": mn * 1e3,
+                    "avg_us": avg * 1e3, "ci95_us": ci * 1e3, "median_us": med * 1e3, "min_us": mn * 1e3,
                     "GB/s": nbytes / (avg * 1e-3) / 1e9, "frac_of_peak": nbytes / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     "Gelem/s": layer.M / (avg * 1e-3) / 1e9,
+                    "warm_single_buffer": {"avg_us": w_avg * 1e3, "ci95_us": w_ci * 1e3, "median_us": w_med * 1e3,
+                                           "min_us": w_mn * 1e3, "GB/s": nbytes / (w_avg * 1e-3) / 1e9},
                 }
 
     paper_micro = None
@@ -337,6 +387,7 @@ def main():
             "hbm_frac_of_peak_whole_step": step_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBS,
         },
         "roofline": roofline,
+        "device": device_report(torch, grkan),
     }
     if detail is not None:
         out["detail"] = detail

@@ -116,6 +116,15 @@ int64_t grkan_plan_cover_errors(int64_t rows, int32_t D, int32_t G, grkan_dtype_
 size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io);
 
 /*
+ * What the HIP runtime reports about the current device, for measurement code
+ * that prices a run against the hardware (no operation of the paper):
+ * out[0] = compute units, out[1] = engine clock in kHz, out[2] = memory clock
+ * in kHz, out[3] = memory bus width in bits.  `out` is a HOST pointer to four
+ * int32.  Returns GRKAN_ERR_NULL or GRKAN_ERR_LAUNCH (a query failed).
+ */
+grkan_status_t grkan_device_query(int32_t *out);
+
+/*
  * Forward (Eq. "pade"):  y[r, c] = P_g(x[r, c]) / (1 + |Aden_g(x[r, c])|).
  * y may alias x.
  */

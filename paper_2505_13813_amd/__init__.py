@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     GRKAN_F32,
     GrkanError,
     Plan,
+    device_query,
     grkan_alg1_bwd,
     grkan_bwd,
     grkan_bwd_raw,

@@ -66,6 +66,8 @@ def load_library():
     lib.grkan_plan.restype = ctypes.c_int
     lib.grkan_plan_cover_errors.argtypes = [i64, i32, i32, ctypes.c_int, ctypes.POINTER(Plan)]
     lib.grkan_plan_cover_errors.restype = i64
+    lib.grkan_device_query.argtypes = [ctypes.POINTER(ctypes.c_int32)]
+    lib.grkan_device_query.restype = ctypes.c_int
     lib.grkan_bwd_workspace_bytes.argtypes = [i64, i32, i32, ctypes.c_int]
     lib.grkan_bwd_workspace_bytes.restype = sz
     lib.grkan_fwd.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, ctypes.c_int, vp]
@@ -99,6 +101,15 @@ def plan_cover_errors(rows: int, D: int, G: int, io: int, p: Plan) -> int:
 
 
 # ---------------------------------------------------------------- raw pointer level
+def device_query() -> dict:
+    """Compute units, engine clock, memory clock (kHz) and memory bus width (bits) of the current device."""
+    out = (ctypes.c_int32 * 4)()
+    st = load_library().grkan_device_query(out)
+    if st != 0:
+        raise GrkanError(st, "grkan_device_query")
+    return {"compute_units": out[0], "engine_clock_khz": out[1], "memory_clock_khz": out[2], "memory_bus_bits": out[3]}
+
+
 def grkan_bwd_workspace_bytes(rows: int, D: int, G: int, io: int) -> int:
     return int(load_library().grkan_bwd_workspace_bytes(rows, D, G, io))
 

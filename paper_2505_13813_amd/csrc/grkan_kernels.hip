@@ -804,6 +804,24 @@ extern "C" size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, 
     return need;
 }
 
+extern "C" grkan_status_t grkan_device_query(int32_t *out)
+{
+    if (!out)
+        return GRKAN_ERR_NULL;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess)
+        return GRKAN_ERR_LAUNCH;
+    const hipDeviceAttribute_t what[4] = {hipDeviceAttributeMultiprocessorCount, hipDeviceAttributeClockRate,
+                                          hipDeviceAttributeMemoryClockRate, hipDeviceAttributeMemoryBusWidth};
+    for (int i = 0; i < 4; ++i) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, what[i], dev) != hipSuccess)
+            return GRKAN_ERR_LAUNCH;
+        out[i] = v;
+    }
+    return GRKAN_OK;
+}
+
 extern "C" grkan_status_t grkan_fwd(const void *x, const float *A, const float *B, void *y,
                                     int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
                                     grkan_dtype_t io, void *hip_stream)
