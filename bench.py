@@ -11,7 +11,12 @@ other configurations; the one-tensor ones run fwd(x) bwd(x).)
 inputs resident in HBM.  Successive steps rotate over several buffer sets per layer so
 that no launch finds its inputs in the 256 MB last-level cache.
 
-Prints ONE JSON line (see the design doc for the field definitions).
+Prints ONE JSON line: metric/value/unit (elements per second through forward+backward),
+ms_per_step, `roofline` (the dominant kernel, the backward of the widest tensor, priced
+against the HBM peak for float32 I/O and against the vector-ALU issue rate for bfloat16 I/O),
+`device` (what the runtime reports), `detail` (per-kernel timings), `paper_micro_benchmark`
+(the shape of the paper's kernel benchmark) and `cpu_baseline` (the fp64 CPU oracle timed on
+the host cores).
 """
 from __future__ import annotations
 
@@ -27,7 +32,9 @@ sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: 256 CUs x 64 lanes x 2.4 GHz, unpacked float32
-BWD_VALU_SLOTS_BF16 = 49  # issue slots per element of the bf16 backward loop (counted in the ISA; rcp = 4)
+# Vector-ALU issue slots per element of the backward loop for 16-bit I/O (instructions counted in
+# the ISA and confirmed with the SQ_INSTS_VALU counter; the quarter-rate reciprocal counts as 4).
+BWD_VALU_SLOTS_16BIT = {("bf16", 5, 4): 49}
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); the
@@ -45,7 +52,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="kat_b", choices=["tiny", "kat_t", "kat_s", "kat_b", "stress"])
     ap.add_argument("--groups", type=int, default=0, help="override the number of groups (stress: 1, 8 or 64)")
-    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16", "f16"])
+    ap.add_argument("--degrees", default="5,4", help="m,n of the rational function: 5,4 (the paper's), 3,2 or 7,6")
     ap.add_argument("--sets", type=int, default=0,
                     help="buffer sets each layer rotates over (0 = enough that one rotation of the smallest "
                          "kernel moves more than 1.1 GB, i.e. several times the 256 MB last-level cache)")
@@ -212,7 +220,12 @@ def main():
 
     cfg = grkan_inputs.CONFIGS[args.workload]
     G = args.groups if args.groups > 0 else cfg.G
-    cases = [grkan_inputs.make_case(args.workload, t, G=G, dtype=args.dtype) for t, _ in cfg.tensors]
+    m_deg, n_deg = (int(v) for v in args.degrees.split(","))
+    if (m_deg, n_deg) not in grkan.DEGREES:
+        print("bench.py: degrees must be one of %s" % (grkan.DEGREES,), file=sys.stderr)
+        sys.exit(2)
+    cases = [grkan_inputs.make_case(args.workload, t, G=G, dtype=args.dtype, m=m_deg, n=n_deg)
+             for t, _ in cfg.tensors]
     layers = [Layer(c, args.sets, torch, grkan) for c in cases]
     names = [t for t, _ in cfg.tensors]
     dom = layers[-1]  # the widest tensor: its backward pass is the dominant kernel
@@ -249,8 +262,11 @@ def main():
     step_bytes = sum(layer.fwd_bytes() + layer.bwd_bytes() for layer in layers)
     dom_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
     key = "%s/%s/bwd_%s" % (args.workload, args.dtype, dom_name)
+    if (m_deg, n_deg) != (5, 4):
+        key += "/%d,%d" % (m_deg, n_deg)
+    slots = BWD_VALU_SLOTS_16BIT.get((args.dtype, m_deg, n_deg))
     what = "grkan_bwd on %s [%d,%d] (stage 1 + stage 2)" % (dom_name, dom.rows, dom.D)
-    if args.dtype == "f32":
+    if args.dtype == "f32" or slots is None:
         achieved = dom.bwd_bytes() / (dom_ms * 1e-3) / 1e9
         roofline = {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -258,15 +274,15 @@ def main():
             "kernel": "%s, %d algorithmic bytes per launch, avg %.2f us" % (what, dom.bwd_bytes(), dom_ms * 1e3),
         }
     else:
-        # bf16 I/O halves the bytes but not the arithmetic: the backward pass is bound by the vector ALU.
+        # 16-bit I/O halves the bytes but not the arithmetic: the backward pass is bound by the vector ALU.
         # Peak = 256 CUs x 64 lanes x 2.4 GHz, one (unpacked) float32 operation per lane and clock.
-        ops = BWD_VALU_SLOTS_BF16 * dom.M
+        ops = slots * dom.M
         achieved = ops / (dom_ms * 1e-3) / 1e12
         roofline = {
             "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TOPS, "unit": "T lane-op/s",
             "frac": achieved / VALU_PEAK_TOPS, "traffic": None,
             "kernel": "%s, %d vector-ALU issue slots per element x %d elements per launch, avg %.2f us "
-                      "(HBM side: %.0f GB/s)" % (what, BWD_VALU_SLOTS_BF16, dom.M, dom_ms * 1e3,
+                      "(HBM side: %.0f GB/s)" % (what, slots, dom.M, dom_ms * 1e3,
                                                   dom.bwd_bytes() / (dom_ms * 1e-3) / 1e9),
         }
 
@@ -300,7 +316,7 @@ def main():
                 }
 
     paper_micro = None
-    if not args.no_paper_micro and args.dtype == "f32":
+    if not args.no_paper_micro and args.dtype == "f32" and (m_deg, n_deg) == (5, 4):
         # The paper's own kernel benchmark (Sec. "Insight 2" / Table 2 and Table 3): X, dO of shape
         # [1024, 197, 768], 8 groups; it reports 4.89 ms forward (KAT CUDA kernel) and 7.33 ms backward
         # (FlashKAT, Triton; 1.03 s with the atomics) on an RTX 4060 Ti.  Seeded N(0,1) inputs drawn on the GPU.
@@ -328,7 +344,7 @@ def main():
         del xs, dys, outs
 
     alg1 = None
-    if args.alg1_baseline and args.dtype == "f32":
+    if args.alg1_baseline and args.dtype == "f32" and (m_deg, n_deg) == (5, 4):
         # the paper's "before": Table 3 reports 1.03 s against 7.33 ms (140.5x) on an RTX 4060 Ti
         alg1 = {}
         for name, layer in zip(names, layers):
@@ -379,9 +395,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {
-            "workload": "%s: fwd+bwd of %s, G=%d, degrees (5,4)"
+            "workload": "%s: fwd+bwd of %s, G=%d, degrees (%d,%d)"
                         % (args.workload, " and ".join("%s [%d,197,%d]" % (n, cfg.batch, l.D)
-                                                       for n, l in zip(names, layers)), G),
+                                                       for n, l in zip(names, layers)), G, m_deg, n_deg),
             "elements_per_step": elems_per_step, "buffer_sets": {n: l.sets for n, l in zip(names, layers)},
             "hbm_GBs_whole_step": step_bytes / (dt / args.steps) / 1e9,
             "hbm_frac_of_peak_whole_step": step_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBS,

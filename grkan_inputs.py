@@ -20,8 +20,11 @@ Recipe (fixed, so every consumer sees the same arrays):
   * x ~ N(0, 1) (or Student-t with 3 degrees of freedom, z / sqrt(chi2_3 / 3),
     for the stress config), dy ~ N(0, sigma^2); x and dy are drawn and stored
     as float32, A and B are drawn as float64 and stored as float32
-  * bf16 variants: the float32 arrays rounded to nearest-even bfloat16; both
-    the uint16 bit patterns and their exact float32 widening are returned
+  * bf16 / f16 variants: the float32 arrays rounded to nearest-even bfloat16 /
+    IEEE binary16; both the uint16 bit patterns and their exact float32
+    widening are returned
+  * other degrees (m, n): the same two child streams with the shapes
+    [G, m + 1] / [G, n] and the same scaling 1 / (i + 1)
   * a sweep over G redraws A and B from the same two child streams with the
     new shape [G, 6] / [G, 4]; x and dy do not depend on G.
 """
@@ -87,13 +90,24 @@ def _streams(cfg: Config):
     return [np.random.Generator(np.random.PCG64(k)) for k in kids]
 
 
-def coefficients(cfg: Config, G: Optional[int] = None) -> Tuple[np.ndarray, np.ndarray]:
-    """(A[G, 6], B[G, 4]) as float32."""
+def coefficients(cfg: Config, G: Optional[int] = None, m: int = M_DEGREE,
+                 n: int = N_DEGREE) -> Tuple[np.ndarray, np.ndarray]:
+    """(A[G, m + 1], B[G, n]) as float32."""
     G = cfg.G if G is None else int(G)
     gens = _streams(cfg)
-    A = gens[0].uniform(-1.0, 1.0, size=(G, M_DEGREE + 1)) / (np.arange(M_DEGREE + 1) + 1.0)
-    B = gens[1].uniform(-0.5, 0.5, size=(G, N_DEGREE))
+    A = gens[0].uniform(-1.0, 1.0, size=(G, m + 1)) / (np.arange(m + 1) + 1.0)
+    B = gens[1].uniform(-0.5, 0.5, size=(G, n))
     return A.astype(np.float32), B.astype(np.float32)
+
+
+def round_to_f16_bits(a: np.ndarray) -> np.ndarray:
+    """float32 -> IEEE binary16 bit patterns (uint16), round to nearest, ties to even."""
+    return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Exact widening of binary16 bit patterns to float32."""
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
 
 
 def _draw_x(gen: np.random.Generator, aux: np.random.Generator, dist: str, shape) -> np.ndarray:
@@ -107,12 +121,13 @@ def _draw_x(gen: np.random.Generator, aux: np.random.Generator, dist: str, shape
 
 
 def make_case(config: str, tensor: Optional[str] = None, G: Optional[int] = None,
-              dtype: str = "f32", rows: Optional[int] = None) -> dict:
+              dtype: str = "f32", rows: Optional[int] = None, m: int = M_DEGREE, n: int = N_DEGREE) -> dict:
     """Build one test/bench case.
 
     Returns a dict with A, B (float32), x, dy (float32, [rows, D]; for
-    dtype="bf16" these hold exactly bf16-representable values and `x_bits`,
-    `dy_bits` hold the uint16 patterns), and the scalars rows, D, G.
+    dtype="bf16" / "f16" these hold exactly representable values of that format
+    and `x_bits`, `dy_bits` hold the uint16 patterns), and the scalars rows, D,
+    G, m, n.
     `rows` cuts the case to its first rows (the stream is drawn row-major, so a
     shorter case is a prefix of the full one).
     """
@@ -121,8 +136,8 @@ def make_case(config: str, tensor: Optional[str] = None, G: Optional[int] = None
     tensor = names[0] if tensor is None else tensor
     if tensor not in names:
         raise ValueError("config %s has tensors %s" % (config, names))
-    if dtype not in ("f32", "bf16"):
-        raise ValueError("dtype must be 'f32' or 'bf16'")
+    if dtype not in ("f32", "bf16", "f16"):
+        raise ValueError("dtype must be 'f32', 'bf16' or 'f16'")
     ti = names.index(tensor)
     D = cfg.D(tensor)
     G = cfg.G if G is None else int(G)
@@ -133,33 +148,37 @@ def make_case(config: str, tensor: Optional[str] = None, G: Optional[int] = None
         raise ValueError("rows must be in [0, %d]" % cfg.rows)
 
     gens = _streams(cfg)
-    A, B = coefficients(cfg, G)
+    A, B = coefficients(cfg, G, m, n)
     x = _draw_x(gens[2 + 3 * ti], gens[4 + 3 * ti], cfg.x_dist, (nrows, D))
     dy = gens[3 + 3 * ti].standard_normal(size=(nrows, D), dtype=np.float32)
     dy *= np.float32(cfg.dy_sigma)
 
     case = dict(config=config, tensor=tensor, dtype=dtype, rows=nrows, D=D, G=G,
-                m=M_DEGREE, n=N_DEGREE, A=A, B=B)
+                m=int(m), n=int(n), A=A, B=B)
     if dtype == "bf16":
         xb, dyb = round_to_bf16_bits(x), round_to_bf16_bits(dy)
         case.update(x_bits=xb, dy_bits=dyb, x=bf16_bits_to_f32(xb), dy=bf16_bits_to_f32(dyb))
+    elif dtype == "f16":
+        xb, dyb = round_to_f16_bits(x), round_to_f16_bits(dy)
+        case.update(x_bits=xb, dy_bits=dyb, x=f16_bits_to_f32(xb), dy=f16_bits_to_f32(dyb))
     else:
         case.update(x=x, dy=dy)
     return case
 
 
 def upload(case: dict, device: str = "cuda:0") -> dict:
-    """Copy a case to the GPU as torch tensors (A, B float32; x, dy float32 or
-    bfloat16 from the stored bit patterns).  Data movement only."""
+    """Copy a case to the GPU as torch tensors (A, B float32; x, dy float32, or
+    bfloat16 / float16 from the stored bit patterns).  Data movement only."""
     import torch
 
     dev = {}
     for k in ("A", "B"):
         dev[k] = torch.from_numpy(np.ascontiguousarray(case[k])).to(device)
     for k in ("x", "dy"):
-        if case["dtype"] == "bf16":
+        if case["dtype"] in ("bf16", "f16"):
             bits = np.ascontiguousarray(case[k + "_bits"]).view(np.int16)
-            dev[k] = torch.from_numpy(bits).to(device).view(torch.bfloat16)
+            dev[k] = torch.from_numpy(bits).to(device).view(
+                torch.bfloat16 if case["dtype"] == "bf16" else torch.float16)
         else:
             dev[k] = torch.from_numpy(np.ascontiguousarray(case[k])).to(device)
     return dev

@@ -7,26 +7,28 @@
  * "grad_b", "grad_x", summed as in Eq. "accum" and "accum2"):
  *
  *     channel c of a row uses coefficient row g = c div d_g,  d_g = D / G
- *     P(x)    = a_{g,0} + a_{g,1} x + ... + a_{g,5} x^5
- *     Aden(x) = b_{g,1} x + ... + b_{g,4} x^4        (the paper writes A(x))
+ *     P(x)    = a_{g,0} + a_{g,1} x + ... + a_{g,m} x^m          (the paper: m = 5)
+ *     Aden(x) = b_{g,1} x + ... + b_{g,n} x^n    (the paper writes A(x); n = 4)
  *     F(x)    = P(x) / (1 + |Aden(x)|)
  *
  * Common conventions of every entry point
  *   - x, y, dy, dx: DEVICE pointers to contiguous row-major [rows, D] arrays of
  *     the I/O dtype `io` (the paper's [B, N, d] tensor with B and N flattened).
- *   - A: DEVICE pointer, float32 [G, 6], A[g*6 + i] = a_{g,i}, i = 0..5.
- *     B: DEVICE pointer, float32 [G, 4], B[g*4 + (j-1)] = b_{g,j}, j = 1..4
+ *   - A: DEVICE pointer, float32 [G, m+1], A[g*(m+1) + i] = a_{g,i}, i = 0..m.
+ *     B: DEVICE pointer, float32 [G, n], B[g*n + (j-1)] = b_{g,j}, j = 1..n
  *     (there is no b_0).  Coefficients and their gradients are float32 for
- *     every I/O dtype; all arithmetic is float32.
+ *     every I/O dtype; all arithmetic is float32 (the denominator polynomial
+ *     is evaluated in double for float32 I/O).
  *   - The caller owns every buffer.  The library never allocates, frees or
  *     keeps device memory.
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*,
  *     NULL = the default stream) and return without synchronising.  The
  *     status reports argument and launch errors only.
- *   - Only (m, n) = (5, 4) is built; other degrees return GRKAN_ERR_DEGREE.
+ *   - Built degrees: (m, n) = (5, 4), the paper's, and its neighbours (3, 2)
+ *     and (7, 6); any other pair returns GRKAN_ERR_DEGREE.
  *   - D % G != 0 is GRKAN_ERR_SHAPE.  rows == 0 is valid.
  *   - Pointers must be aligned to the element size.  16-byte aligned tensors
- *     with d_g a multiple of 4 (float32) or 8 (bfloat16) take the fast
+ *     with d_g a multiple of 4 (float32) or 8 (16-bit formats) take the fast
  *     128-bit path; anything else silently takes a narrower-vector variant.
  */
 #ifndef GRKAN_H_
@@ -40,15 +42,17 @@ extern "C" {
 #endif
 
 typedef enum {
-    GRKAN_F32 = 0, /* x, y, dy, dx are float32 */
-    GRKAN_BF16 = 1 /* x, y, dy, dx are bfloat16; outputs rounded to nearest even */
+    GRKAN_F32 = 0,  /* x, y, dy, dx are float32 */
+    GRKAN_BF16 = 1, /* x, y, dy, dx are bfloat16; outputs rounded to nearest even */
+    GRKAN_F16 = 2   /* x, y, dy, dx are IEEE binary16; outputs rounded to nearest even,
+                       results beyond 65504 in magnitude become infinities */
 } grkan_dtype_t;
 
 typedef enum {
     GRKAN_OK = 0,
     GRKAN_ERR_NULL = 1,      /* a required pointer is NULL */
     GRKAN_ERR_SHAPE = 2,     /* rows < 0, D <= 0, G <= 0 or D % G != 0 */
-    GRKAN_ERR_DEGREE = 3,    /* (m, n) != (5, 4) */
+    GRKAN_ERR_DEGREE = 3,    /* (m, n) is not one of the built degree pairs */
     GRKAN_ERR_ALIGN = 4,     /* a pointer is not aligned to its element size */
     GRKAN_ERR_WORKSPACE = 5, /* workspace missing or smaller than required */
     GRKAN_ERR_DTYPE = 6,     /* unknown grkan_dtype_t */
@@ -83,7 +87,7 @@ typedef struct {
     int32_t grid;                 /* workgroups launched = (walk groups / groups_per_wg) * wg_per_bundle */
     int32_t fixed_col;            /* 1: every lane keeps its column for the whole kernel */
     int64_t chunk_stride;         /* 64-vector chunks between two visits of one wavefront */
-    int32_t partials_per_group;   /* rows of 10 floats each group contributes to the workspace */
+    int32_t partials_per_group;   /* rows of m+1+n floats each group contributes to the workspace */
     int32_t lane_coef;            /* 1: flat walk with per-lane coefficients (then fixed_col = 1) */
 } grkan_plan_t;
 
@@ -110,8 +114,8 @@ int64_t grkan_plan_cover_errors(int64_t rows, int32_t D, int32_t G, grkan_dtype_
 
 /*
  * Bytes of device workspace grkan_bwd needs for this shape on the current
- * device (an upper bound over every alignment of the tensors).  Needs a HIP
- * device; returns 0 on any error.
+ * device (an upper bound over every alignment of the tensors and every built
+ * degree pair).  Needs a HIP device; returns 0 on any error.
  */
 size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io);
 
@@ -140,7 +144,7 @@ grkan_status_t grkan_fwd(const void *x, const float *A, const float *B, void *y,
  *   dA[g, i]  = sum over all rows and the d_g channels of group g of  dy * x^i / Q
  *   dB[g, j-1]= sum over the same elements of                       -dy * x^j * s * P / Q^2
  *
- * dA (float32 [G, 6]) and dB (float32 [G, 4]) are OVERWRITTEN with the sums.
+ * dA (float32 [G, m+1]) and dB (float32 [G, n]) are OVERWRITTEN with the sums.
  * The sums use no atomic operations and a fixed order: for one build, device,
  * shape and pointer alignment the results are bit-identical from run to run.
  * dx may alias dy or x.  `workspace` is device scratch of at least

@@ -4,7 +4,9 @@ The product is libgrkan.so (hand-written HIP for gfx950 behind the C ABI in
 include/grkan.h); this package is its thin Python binding.
 """
 from .binding import (  # noqa: F401
+    DEGREES,
     GRKAN_BF16,
+    GRKAN_F16,
     GRKAN_F32,
     GrkanError,
     Plan,

@@ -16,8 +16,10 @@ LIB_PATH = _PKG / "libgrkan.so"
 
 GRKAN_F32 = 0
 GRKAN_BF16 = 1
-M_DEGREE = 5
+GRKAN_F16 = 2
+M_DEGREE = 5  # the paper's degrees; (3, 2) and (7, 6) are built too
 N_DEGREE = 4
+DEGREES = ((5, 4), (3, 2), (7, 6))
 
 _lib = None
 
@@ -58,6 +60,11 @@ def load_library():
         from . import build as _build
 
         _build.build_library(force=True)
+    # torch first: it ships its own copy of the HIP runtime under the same soname as the
+    # system's.  Whichever is loaded first serves the whole process, and the tensors this
+    # library is handed live in torch's; loaded the other way round, launches on them fail.
+    import torch  # noqa: F401
+
     lib = ctypes.CDLL(str(LIB_PATH))
     vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
     lib.grkan_status_string.argtypes = [ctypes.c_int]
@@ -132,7 +139,9 @@ def _io_of(t) -> int:
         return GRKAN_F32
     if t.dtype == torch.bfloat16:
         return GRKAN_BF16
-    raise TypeError("x must be float32 or bfloat16, got %s" % t.dtype)
+    if t.dtype == torch.float16:
+        return GRKAN_F16
+    raise TypeError("x must be float32, bfloat16 or float16, got %s" % t.dtype)
 
 
 def _check(x, A, B) -> Tuple[int, int, int]:

@@ -26,6 +26,7 @@
 #include <cstdlib>
 #include <mutex>
 #include <tuple>
+#include <type_traits>
 #include <vector>
 
 #include "grkan_plan.h"
@@ -33,27 +34,35 @@
 namespace grkan {
 
 // --------------------------------------------------------------------------
-// coefficients of one group (scalar registers when the group is wave-uniform,
-// vector registers in the flat walk)
+// coefficients of one group for numerator degree M and denominator degree N
+// (scalar registers when the group is wave-uniform, vector registers in the
+// flat walk).  Entries no kernel reads cost nothing: everything is unrolled.
 // --------------------------------------------------------------------------
-struct Coef {
-    float a0, a1, a2, a3, a4, a5;
-    float b1, b2, b3, b4;
-    float da2, da3, da4, da5; // i * a_i, the coefficients of P'
-    float db2, db3, db4;      // j * b_j, the coefficients of Aden'
-    double b1d, b2d, b3d, b4d; // for the float32-I/O kernels, which evaluate Aden in double (see aden_of)
+template <int M, int N> struct Coef {
+    float a[M + 1];  // a_0 .. a_M
+    float b[N];      // b_1 .. b_N  (b[j - 1] = b_j)
+    float da[M + 1]; // i * a_i, the coefficients of P'  (da[0] unused)
+    float db[N];     // j * b_j, the coefficients of Aden'
+    double bd[N];    // b_j in double, for the float32-I/O kernels (see aden_of)
 };
 
-__device__ __forceinline__ Coef load_coef(const float *__restrict__ A, const float *__restrict__ B, int g)
+template <int M, int N>
+__device__ __forceinline__ Coef<M, N> load_coef(const float *__restrict__ A, const float *__restrict__ B, int g)
 {
-    const float *a = A + (size_t)g * 6;
-    const float *b = B + (size_t)g * 4;
-    Coef c;
-    c.a0 = a[0]; c.a1 = a[1]; c.a2 = a[2]; c.a3 = a[3]; c.a4 = a[4]; c.a5 = a[5];
-    c.b1 = b[0]; c.b2 = b[1]; c.b3 = b[2]; c.b4 = b[3];
-    c.da2 = 2.0f * c.a2; c.da3 = 3.0f * c.a3; c.da4 = 4.0f * c.a4; c.da5 = 5.0f * c.a5;
-    c.db2 = 2.0f * b[1]; c.db3 = 3.0f * b[2]; c.db4 = 4.0f * b[3];
-    c.b1d = (double)b[0]; c.b2d = (double)b[1]; c.b3d = (double)b[2]; c.b4d = (double)b[3];
+    const float *a = A + (size_t)g * (M + 1);
+    const float *b = B + (size_t)g * N;
+    Coef<M, N> c;
+#pragma unroll
+    for (int i = 0; i <= M; ++i) {
+        c.a[i] = a[i];
+        c.da[i] = i >= 2 ? (float)i * a[i] : a[i];
+    }
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        c.b[j] = b[j];
+        c.db[j] = j >= 1 ? (float)(j + 1) * b[j] : b[j];
+        c.bd[j] = (double)b[j];
+    }
     return c;
 }
 
@@ -61,7 +70,7 @@ __device__ __forceinline__ Coef load_coef(const float *__restrict__ A, const flo
 // per-element arithmetic (float32)
 // --------------------------------------------------------------------------
 
-// Aden = x (b1 + b2 x + b3 x^2 + b4 x^3) by Horner.
+// Aden = x (b_1 + b_2 x + ... + b_N x^(N-1)) by Horner.
 //
 // WIDE = true (float32 I/O): in double, rounded once to float32.  Q = 1 + |Aden|
 // sits in every result as 1/Q or 1/Q^2, and next to a real root of the
@@ -73,88 +82,93 @@ __device__ __forceinline__ Coef load_coef(const float *__restrict__ A, const flo
 // absolute error with N(0,1) coefficients).  Double FMA issues at the unpacked
 // float32 rate on this chip, and the float32-I/O kernels are bound by HBM, so
 // this is free there.
-// WIDE = false (bfloat16 I/O): in float32.  That backward kernel is bound by
+// WIDE = false (16-bit I/O): in float32.  That backward kernel is bound by
 // the vector ALU (the conversions and double compares cost it 12 %), and its
-// outputs are rounded to 8 mantissa bits anyway.
-template <bool WIDE> __device__ __forceinline__ float aden_of(float x, const Coef &c)
+// outputs are rounded to 8 or 11 significant bits anyway.
+template <bool WIDE, int M, int N> __device__ __forceinline__ float aden_of(float x, const Coef<M, N> &c)
 {
     if constexpr (WIDE) {
         const double xd = (double)x;
-        double h = fma(c.b4d, xd, c.b3d);
-        h = fma(h, xd, c.b2d);
-        h = fma(h, xd, c.b1d);
+        double h = c.bd[N - 1];
+#pragma unroll
+        for (int j = N - 2; j >= 0; --j)
+            h = fma(h, xd, c.bd[j]);
         return (float)(h * xd);
     } else {
-        float h = fmaf(c.b4, x, c.b3);
-        h = fmaf(h, x, c.b2);
-        h = fmaf(h, x, c.b1);
+        float h = c.b[N - 1];
+#pragma unroll
+        for (int j = N - 2; j >= 0; --j)
+            h = fmaf(h, x, c.b[j]);
         return h * x;
     }
 }
 
+template <int M, int N> __device__ __forceinline__ float numerator_of(float x, const Coef<M, N> &c)
+{
+    float p = c.a[M];
+#pragma unroll
+    for (int i = M - 1; i >= 0; --i)
+        p = fmaf(p, x, c.a[i]);
+    return p;
+}
+
 // Eq. "pade": P by Horner in float32, Aden as above, and one hardware
 // reciprocal (1 ulp) instead of a division.
-template <bool WIDE> __device__ __forceinline__ float fwd_elem(float x, const Coef &c)
+template <bool WIDE, int M, int N> __device__ __forceinline__ float fwd_elem(float x, const Coef<M, N> &c)
 {
-    float p = fmaf(c.a5, x, c.a4);
-    p = fmaf(p, x, c.a3);
-    p = fmaf(p, x, c.a2);
-    p = fmaf(p, x, c.a1);
-    p = fmaf(p, x, c.a0);
+    const float p = numerator_of(x, c);
     const float aden = aden_of<WIDE>(x, c);
     const float q = 1.0f + fabsf(aden);
     return p * __builtin_amdgcn_rcpf(q);
 }
 
 // Eq. "grad_x", "grad_a", "grad_b" for one element; returns dx and adds this
-// element's ten terms to acc (acc[0..5] numerator, acc[6..9] denominator, the
-// latter with the opposite sign until negate_b_sums is applied).
-// P/Q^2 is formed as (P r) r with r = 1/Q, so Q^2 is never computed.
-template <bool WIDE>
-__device__ __forceinline__ float bwd_elem(float x, float d, const Coef &c, float (&acc)[kNumCoef])
+// element's M + 1 + N terms to acc (acc[0..M] numerator, acc[M+1..M+N]
+// denominator, the latter with the opposite sign until negate_b_sums is
+// applied).  P/Q^2 is formed as (P r) r with r = 1/Q, so Q^2 is never computed.
+template <bool WIDE, int M, int N>
+__device__ __forceinline__ float bwd_elem(float x, float d, const Coef<M, N> &c, float (&acc)[M + 1 + N])
 {
-    const float x2 = x * x;
-    const float x3 = x2 * x;
-    const float x4 = x2 * x2;
-    const float x5 = x4 * x;
+    // x^k: squares for even k, one more factor x for odd k
+    constexpr int K = M > N ? M : N;
+    float pw[K + 1];
+    pw[0] = 1.0f;
+    pw[1] = x;
+#pragma unroll
+    for (int k = 2; k <= K; ++k)
+        pw[k] = (k % 2 == 0) ? pw[k / 2] * pw[k / 2] : pw[k - 1] * x;
 
-    float p = fmaf(c.a5, x, c.a4);
-    p = fmaf(p, x, c.a3);
-    p = fmaf(p, x, c.a2);
-    p = fmaf(p, x, c.a1);
-    p = fmaf(p, x, c.a0);
+    const float p = numerator_of(x, c);
 
-    float dp = fmaf(c.da5, x, c.da4);
-    dp = fmaf(dp, x, c.da3);
-    dp = fmaf(dp, x, c.da2);
-    dp = fmaf(dp, x, c.a1);
+    float dp = c.da[M];
+#pragma unroll
+    for (int i = M - 1; i >= 1; --i)
+        dp = fmaf(dp, x, c.da[i]);
 
     const float aden = aden_of<WIDE>(x, c);
 
-    float dh = fmaf(c.db4, x, c.db3);
-    dh = fmaf(dh, x, c.db2);
-    dh = fmaf(dh, x, c.b1);
+    float dh = c.db[N - 1];
+#pragma unroll
+    for (int j = N - 2; j >= 0; --j)
+        dh = fmaf(dh, x, c.db[j]);
 
     const float q = 1.0f + fabsf(aden);
     const float r = __builtin_amdgcn_rcpf(q);
 
     const float t = d * r; // dy / Q
     acc[0] += t;
-    acc[1] = fmaf(t, x, acc[1]);
-    acc[2] = fmaf(t, x2, acc[2]);
-    acc[3] = fmaf(t, x3, acc[3]);
-    acc[4] = fmaf(t, x4, acc[4]);
-    acc[5] = fmaf(t, x5, acc[5]);
+#pragma unroll
+    for (int i = 1; i <= M; ++i)
+        acc[i] = fmaf(t, pw[i], acc[i]);
 
     // s / Q with s = sign(Aden), sign(0) = 0: r > 0, so the sign is copied onto it bitwise
     const float sr = aden != 0.0f ? __builtin_copysignf(r, aden) : 0.0f;
-    // acc[6..9] collect +dy s P x^j / Q^2; the minus sign of Eq. "grad_b" is
+    // acc[M+1..] collect +dy s P x^j / Q^2; the minus sign of Eq. "grad_b" is
     // applied once per lane after the loop (negate_b_sums)
     const float wb = d * ((p * r) * sr); // dy s P / Q^2
-    acc[6] = fmaf(wb, x, acc[6]);
-    acc[7] = fmaf(wb, x2, acc[7]);
-    acc[8] = fmaf(wb, x3, acc[8]);
-    acc[9] = fmaf(wb, x4, acc[9]);
+#pragma unroll
+    for (int j = 1; j <= N; ++j)
+        acc[M + j] = fmaf(wb, pw[j], acc[M + j]);
 
     // dx = dy (P'/Q - s Aden' P/Q^2) = (dy/Q) P' - (dy s P/Q^2) Aden'
     const float dx = fmaf(t, dp, -(wb * dh));
@@ -177,10 +191,10 @@ __device__ __forceinline__ uint64_t uniform_u64(uint64_t v)
     return ((uint64_t)hi << 32) | lo;
 }
 
-__device__ __forceinline__ void negate_b_sums(float (&acc)[kNumCoef])
+template <int M, int N> __device__ __forceinline__ void negate_b_sums(float (&acc)[M + 1 + N])
 {
 #pragma unroll
-    for (int k = 6; k < kNumCoef; ++k)
+    for (int k = M + 1; k < M + 1 + N; ++k)
         acc[k] = -acc[k];
 }
 
@@ -191,10 +205,57 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
+// tags of the two 16-bit I/O formats (the arithmetic is float32 for both)
 struct bf16_t {
     uint16_t bits;
 };
+struct f16_t {
+    uint16_t bits;
+};
+
+// two 16-bit elements of one 32-bit word -> float32 (element 0 in the low half)
+template <typename IO> __device__ __forceinline__ void widen_pair(uint32_t w, float &lo, float &hi)
+{
+    if constexpr (std::is_same_v<IO, bf16_t>) {
+        // bfloat16 -> float32 is a 16-bit shift
+        lo = __builtin_bit_cast(float, w << 16);
+        hi = __builtin_bit_cast(float, w & 0xffff0000u);
+    } else {
+        const f16x2 h = __builtin_bit_cast(f16x2, w);
+        lo = (float)h[0];
+        hi = (float)h[1];
+    }
+}
+
+// two float32 -> one word of two 16-bit elements, round to nearest even
+template <typename IO> __device__ __forceinline__ uint32_t narrow_pair(float lo, float hi)
+{
+    f32x2 f;
+    f[0] = lo;
+    f[1] = hi;
+    if constexpr (std::is_same_v<IO, bf16_t>)
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+    else
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2));
+}
+
+template <typename IO> __device__ __forceinline__ float widen_one(uint16_t v)
+{
+    if constexpr (std::is_same_v<IO, bf16_t>)
+        return __builtin_bit_cast(float, (uint32_t)v << 16);
+    else
+        return (float)__builtin_bit_cast(_Float16, v);
+}
+
+template <typename IO> __device__ __forceinline__ uint16_t narrow_one(float v)
+{
+    if constexpr (std::is_same_v<IO, bf16_t>)
+        return __builtin_bit_cast(uint16_t, static_cast<__bf16>(v));
+    else
+        return __builtin_bit_cast(uint16_t, static_cast<_Float16>(v));
+}
 
 template <int BYTES> struct RawOf;
 template <> struct RawOf<16> { using type = u32x4; };
@@ -229,15 +290,12 @@ template <typename IO, int VEC> __device__ __forceinline__ void unpack(const Raw
         for (int i = 0; i < VEC; ++i)
             out[i] = __builtin_bit_cast(float, raw_word<BYTES>(r, i));
     } else if constexpr (VEC == 1) {
-        out[0] = __builtin_bit_cast(float, (uint32_t)r << 16);
+        out[0] = widen_one<IO>(r);
     } else {
-        // bfloat16 -> float32 is a 16-bit shift; two elements per 32-bit word
+        // two elements per 32-bit word
 #pragma unroll
-        for (int i = 0; i < VEC / 2; ++i) {
-            const uint32_t w = raw_word<BYTES>(r, i);
-            out[2 * i] = __builtin_bit_cast(float, w << 16);
-            out[2 * i + 1] = __builtin_bit_cast(float, w & 0xffff0000u);
-        }
+        for (int i = 0; i < VEC / 2; ++i)
+            widen_pair<IO>(raw_word<BYTES>(r, i), out[2 * i], out[2 * i + 1]);
     }
 }
 
@@ -260,15 +318,11 @@ template <typename IO, int VEC> __device__ __forceinline__ void store_vec(gptr_t
                 r[i] = __builtin_bit_cast(uint32_t, in[i]);
         }
     } else if constexpr (VEC == 1) {
-        // round to nearest even
-        r = __builtin_bit_cast(uint16_t, static_cast<__bf16>(in[0]));
+        r = narrow_one<IO>(in[0]);
     } else {
 #pragma unroll
         for (int i = 0; i < VEC / 2; ++i) {
-            f32x2 f;
-            f[0] = in[2 * i];
-            f[1] = in[2 * i + 1];
-            const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+            const uint32_t w = narrow_pair<IO>(in[2 * i], in[2 * i + 1]);
             if constexpr (VEC == 2)
                 r = w;
             else
@@ -330,7 +384,7 @@ struct BwdArgs {
 // so that the chip as a whole keeps about 4 MB of loads in flight (measured
 // optimum of this memory system for a streaming read/write mix; both deeper
 // per-wave prefetch and more resident waves were measured slower).
-template <typename IO, int VEC, bool FIXED, bool LANECOEF>
+template <typename IO, int VEC, bool FIXED, bool LANECOEF, int M, int N>
 __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs a)
 {
     static_assert(FIXED || !LANECOEF, "per-lane coefficients need fixed columns");
@@ -341,7 +395,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
     // group walk: the wave's group (scalar registers); flat walk: the group of
     // this lane's fixed column (vector registers)
     const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc) : id.g;
-    const Coef c = load_coef(a.A, a.B, cg);
+    const Coef<M, N> c = load_coef<M, N>(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
     constexpr int64_t ES = sizeof(IO);
@@ -354,7 +408,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
         load_vec<IO, VEC>((gcptr_t)(x0 + off), xv);
 #pragma unroll
         for (int e = 0; e < VEC; ++e)
-            yv[e] = fwd_elem<WIDE>(xv[e], c);
+            yv[e] = fwd_elem<WIDE, M, N>(xv[e], c);
         store_vec<IO, VEC>((gptr_t)(y0 + off), yv);
     };
 
@@ -377,7 +431,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
             float yv[VEC];
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
-                yv[e] = fwd_elem<WIDE>(xs[e], c);
+                yv[e] = fwd_elem<WIDE, M, N>(xs[e], c);
             store_vec<IO, VEC>(yout(it), yv);
             if (more)
                 unpack<IO, VEC>(xn, xs); // the wait for the prefetch lands here
@@ -396,7 +450,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
 }
 
 // Backward, stage 1 (see the file header).
-template <typename IO, int VEC, bool FIXED, bool LANECOEF>
+template <typename IO, int VEC, bool FIXED, bool LANECOEF, int M, int N>
 __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const BwdArgs a)
 {
     static_assert(FIXED || !LANECOEF, "per-lane coefficients need fixed columns");
@@ -405,7 +459,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
     const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc) : id.g;
-    const Coef c = load_coef(a.A, a.B, cg);
+    const Coef<M, N> c = load_coef<M, N>(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
     constexpr int64_t ES = sizeof(IO);
@@ -414,6 +468,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
     const uint64_t dy0 = reinterpret_cast<uint64_t>(a.dy);
     const uint64_t dx0 = reinterpret_cast<uint64_t>(a.dx);
 
+    constexpr int kNumCoef = M + 1 + N; // sums per group
     float acc[kNumCoef];
 #pragma unroll
     for (int k = 0; k < kNumCoef; ++k)
@@ -425,7 +480,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
         load_vec<IO, VEC>((gcptr_t)(dy0 + off), dv);
 #pragma unroll
         for (int e = 0; e < VEC; ++e)
-            ov[e] = bwd_elem<WIDE>(xv[e], dv[e], c, acc);
+            ov[e] = bwd_elem<WIDE, M, N>(xv[e], dv[e], c, acc);
         store_vec<IO, VEC>((gptr_t)(dx0 + off), ov);
     };
 
@@ -453,7 +508,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
             float ov[VEC];
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
-                ov[e] = bwd_elem<WIDE>(xs[e], ds[e], c, acc);
+                ov[e] = bwd_elem<WIDE, M, N>(xs[e], ds[e], c, acc);
             store_vec<IO, VEC>(dxout(it), ov);
             if (more) { // the wait for the prefetch lands here
                 unpack<IO, VEC>(xn, xs);
@@ -472,7 +527,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
             one((uint64_t)(elem_offset(p, id.g, s) * ES));
     }
 
-    negate_b_sums(acc);
+    negate_b_sums<M, N>(acc);
     if constexpr (!LANECOEF) {
         // registers -> wavefront (DPP) -> workgroup (LDS) -> one workspace row per group
         __shared__ float wave_part[kWavesPerWg][kNumCoef];
@@ -543,11 +598,13 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
 // them in lane order.  Every order is fixed; dA / dB are overwritten.
 constexpr int kStage2Threads = kWave;
 
+template <int M, int N>
 __global__ __launch_bounds__(kStage2Threads) void grkan_bwd_stage2_kernel(const float *__restrict__ partial,
                                                                           int32_t rows_per_group,
                                                                           float *__restrict__ dA,
                                                                           float *__restrict__ dB)
 {
+    constexpr int kNumCoef = M + 1 + N;
     __shared__ double lane_sum[kNumCoef][kStage2Threads];
     const int g = blockIdx.x;
     const int tid = threadIdx.x;
@@ -570,10 +627,10 @@ __global__ __launch_bounds__(kStage2Threads) void grkan_bwd_stage2_kernel(const 
         double t = 0.0;
         for (int l = 0; l < kStage2Threads; ++l)
             t += lane_sum[tid][l];
-        if (tid < 6)
-            dA[g * 6 + tid] = (float)t;
+        if (tid <= M)
+            dA[g * (M + 1) + tid] = (float)t;
         else
-            dB[g * 4 + (tid - 6)] = (float)t;
+            dB[g * N + (tid - (M + 1))] = (float)t;
     }
 }
 
@@ -623,60 +680,110 @@ static int32_t common_alignment(std::initializer_list<const void *> ptrs)
     return (int32_t)(bits & (~bits + 1)); // lowest set bit, at most 16
 }
 
-// Kernel selection: the variant for (dtype, vector width, walk mode) as a
-// plain function pointer, so that one code path can both query its occupancy
-// and launch it.
+// Kernel selection: the variant for (degrees, dtype, vector width, walk mode)
+// as a plain function pointer, so that one code path can both query its
+// occupancy and launch it.
 using FwdKernel = void (*)(const FwdArgs);
 using BwdKernel = void (*)(const BwdArgs);
+using Stage2Kernel = void (*)(const float *, int32_t, float *, float *);
 
-template <typename IO, int VEC> static FwdKernel fwd_variant(bool fixed, bool lane_coef)
+template <typename IO, int VEC, int M, int N> static FwdKernel fwd_variant(bool fixed, bool lane_coef)
 {
     if (lane_coef)
-        return grkan_fwd_kernel<IO, VEC, true, true>;
-    return fixed ? grkan_fwd_kernel<IO, VEC, true, false> : grkan_fwd_kernel<IO, VEC, false, false>;
+        return grkan_fwd_kernel<IO, VEC, true, true, M, N>;
+    return fixed ? grkan_fwd_kernel<IO, VEC, true, false, M, N> : grkan_fwd_kernel<IO, VEC, false, false, M, N>;
 }
-template <typename IO, int VEC> static BwdKernel bwd_variant(bool fixed, bool lane_coef)
+template <typename IO, int VEC, int M, int N> static BwdKernel bwd_variant(bool fixed, bool lane_coef)
 {
     if (lane_coef)
-        return grkan_bwd_stage1_kernel<IO, VEC, true, true>;
-    return fixed ? grkan_bwd_stage1_kernel<IO, VEC, true, false> : grkan_bwd_stage1_kernel<IO, VEC, false, false>;
+        return grkan_bwd_stage1_kernel<IO, VEC, true, true, M, N>;
+    return fixed ? grkan_bwd_stage1_kernel<IO, VEC, true, false, M, N>
+                 : grkan_bwd_stage1_kernel<IO, VEC, false, false, M, N>;
 }
 
-static FwdKernel select_fwd(grkan_dtype_t io, int vec, bool fixed, bool lane_coef)
+template <int M, int N> static FwdKernel select_fwd(grkan_dtype_t io, int vec, bool fixed, bool lane_coef)
 {
-    if (io == GRKAN_F32) {
+    switch (io) {
+    case GRKAN_F32:
         switch (vec) {
-        case 4: return fwd_variant<float, 4>(fixed, lane_coef);
-        case 2: return fwd_variant<float, 2>(fixed, lane_coef);
-        case 1: return fwd_variant<float, 1>(fixed, lane_coef);
+        case 4: return fwd_variant<float, 4, M, N>(fixed, lane_coef);
+        case 2: return fwd_variant<float, 2, M, N>(fixed, lane_coef);
+        case 1: return fwd_variant<float, 1, M, N>(fixed, lane_coef);
         }
-    } else {
+        break;
+    case GRKAN_BF16:
         switch (vec) {
-        case 8: return fwd_variant<bf16_t, 8>(fixed, lane_coef);
-        case 4: return fwd_variant<bf16_t, 4>(fixed, lane_coef);
-        case 2: return fwd_variant<bf16_t, 2>(fixed, lane_coef);
-        case 1: return fwd_variant<bf16_t, 1>(fixed, lane_coef);
+        case 8: return fwd_variant<bf16_t, 8, M, N>(fixed, lane_coef);
+        case 4: return fwd_variant<bf16_t, 4, M, N>(fixed, lane_coef);
+        case 2: return fwd_variant<bf16_t, 2, M, N>(fixed, lane_coef);
+        case 1: return fwd_variant<bf16_t, 1, M, N>(fixed, lane_coef);
         }
+        break;
+    case GRKAN_F16:
+        switch (vec) {
+        case 8: return fwd_variant<f16_t, 8, M, N>(fixed, lane_coef);
+        case 4: return fwd_variant<f16_t, 4, M, N>(fixed, lane_coef);
+        case 2: return fwd_variant<f16_t, 2, M, N>(fixed, lane_coef);
+        case 1: return fwd_variant<f16_t, 1, M, N>(fixed, lane_coef);
+        }
+        break;
     }
     return nullptr;
 }
 
-static BwdKernel select_bwd(grkan_dtype_t io, int vec, bool fixed, bool lane_coef)
+template <int M, int N> static BwdKernel select_bwd(grkan_dtype_t io, int vec, bool fixed, bool lane_coef)
 {
-    if (io == GRKAN_F32) {
+    switch (io) {
+    case GRKAN_F32:
         switch (vec) {
-        case 4: return bwd_variant<float, 4>(fixed, lane_coef);
-        case 2: return bwd_variant<float, 2>(fixed, lane_coef);
-        case 1: return bwd_variant<float, 1>(fixed, lane_coef);
+        case 4: return bwd_variant<float, 4, M, N>(fixed, lane_coef);
+        case 2: return bwd_variant<float, 2, M, N>(fixed, lane_coef);
+        case 1: return bwd_variant<float, 1, M, N>(fixed, lane_coef);
         }
-    } else {
+        break;
+    case GRKAN_BF16:
         switch (vec) {
-        case 8: return bwd_variant<bf16_t, 8>(fixed, lane_coef);
-        case 4: return bwd_variant<bf16_t, 4>(fixed, lane_coef);
-        case 2: return bwd_variant<bf16_t, 2>(fixed, lane_coef);
-        case 1: return bwd_variant<bf16_t, 1>(fixed, lane_coef);
+        case 8: return bwd_variant<bf16_t, 8, M, N>(fixed, lane_coef);
+        case 4: return bwd_variant<bf16_t, 4, M, N>(fixed, lane_coef);
+        case 2: return bwd_variant<bf16_t, 2, M, N>(fixed, lane_coef);
+        case 1: return bwd_variant<bf16_t, 1, M, N>(fixed, lane_coef);
         }
+        break;
+    case GRKAN_F16:
+        switch (vec) {
+        case 8: return bwd_variant<f16_t, 8, M, N>(fixed, lane_coef);
+        case 4: return bwd_variant<f16_t, 4, M, N>(fixed, lane_coef);
+        case 2: return bwd_variant<f16_t, 2, M, N>(fixed, lane_coef);
+        case 1: return bwd_variant<f16_t, 1, M, N>(fixed, lane_coef);
+        }
+        break;
     }
+    return nullptr;
+}
+
+// The degrees the library is built for.  (5, 4) is the paper's; (3, 2) and
+// (7, 6) are the neighbouring "numerator one degree above the denominator"
+// units of the same family.
+struct DegreeOps {
+    int m, n;
+    FwdKernel (*fwd)(grkan_dtype_t, int, bool, bool);
+    BwdKernel (*bwd)(grkan_dtype_t, int, bool, bool);
+    Stage2Kernel stage2;
+};
+
+template <int M, int N> static constexpr DegreeOps degree_entry()
+{
+    static_assert(M + 1 + N <= kMaxCoef, "workspace rows are sized for kMaxCoef sums");
+    return DegreeOps{M, N, select_fwd<M, N>, select_bwd<M, N>, grkan_bwd_stage2_kernel<M, N>};
+}
+
+static const DegreeOps kDegrees[] = {degree_entry<5, 4>(), degree_entry<3, 2>(), degree_entry<7, 6>()};
+
+static const DegreeOps *degree_ops(int m, int n)
+{
+    for (const DegreeOps &d : kDegrees)
+        if (d.m == m && d.n == n)
+            return &d;
     return nullptr;
 }
 
@@ -723,7 +830,7 @@ static Want bwd_want(grkan_dtype_t io)
     const int e = env_int("GRKAN_BWD_WG_PER_CU", 0);
     if (e)
         return Want{e, e};
-    return io == GRKAN_F32 ? Want{2, 3} : Want{8, 8};
+    return io == GRKAN_F32 ? Want{2, 3} : Want{8, 8}; // both 16-bit formats are ALU-bound
 }
 
 // Plans the launch with the wanted workgroups per unit, then clamps to what
@@ -767,16 +874,19 @@ static grkan_status_t plan_resident(int64_t rows, int32_t D, int32_t G, grkan_dt
     return GRKAN_OK;
 }
 
-static grkan_status_t check_common(int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n, grkan_dtype_t io)
+static grkan_status_t check_common(int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n, grkan_dtype_t io,
+                                   const DegreeOps **ops)
 {
-    if (m != 5 || n != 4)
+    *ops = degree_ops(m, n);
+    if (!*ops)
         return GRKAN_ERR_DEGREE;
     return check_shape(rows, D, G, io);
 }
 
-static size_t workspace_for(const grkan_plan_t &pl, int32_t G)
+// rows of `coefs` floats, one per (group, workgroup that holds a part of it)
+static size_t workspace_for(const grkan_plan_t &pl, int32_t G, int coefs)
 {
-    return (size_t)G * (size_t)pl.partials_per_group * kNumCoef * sizeof(float);
+    return (size_t)G * (size_t)pl.partials_per_group * (size_t)coefs * sizeof(float);
 }
 
 } // namespace grkan
@@ -792,14 +902,17 @@ extern "C" size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, 
     if (!device_info(&dev, &info))
         return 0;
     size_t need = 16; // never zero, so that callers can always allocate it
-    for (int align = elem_size(io); align <= 16; align *= 2) {
-        grkan_plan_t pl;
-        const void *kernel = nullptr;
-        if (plan_resident(rows, D, G, io, align, info, dev, bwd_want(io), false, select_bwd, &pl, nullptr, &kernel) !=
-            GRKAN_OK)
-            return 0;
-        const size_t b = workspace_for(pl, G);
-        need = b > need ? b : need;
+    // the query names no degrees: the bound covers every built (m, n), whose kernels differ in occupancy
+    for (const DegreeOps &ops : kDegrees) {
+        for (int align = elem_size(io); align <= 16; align *= 2) {
+            grkan_plan_t pl;
+            const void *kernel = nullptr;
+            if (plan_resident(rows, D, G, io, align, info, dev, bwd_want(io), false, ops.bwd, &pl, nullptr, &kernel) !=
+                GRKAN_OK)
+                return 0;
+            const size_t b = workspace_for(pl, G, ops.m + 1 + ops.n);
+            need = b > need ? b : need;
+        }
     }
     return need;
 }
@@ -826,7 +939,8 @@ extern "C" grkan_status_t grkan_fwd(const void *x, const float *A, const float *
                                     int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
                                     grkan_dtype_t io, void *hip_stream)
 {
-    grkan_status_t st = check_common(rows, D, G, m, n, io);
+    const DegreeOps *ops = nullptr;
+    grkan_status_t st = check_common(rows, D, G, m, n, io, &ops);
     if (st != GRKAN_OK)
         return st;
     if (!A || !B || (rows > 0 && (!x || !y)))
@@ -845,7 +959,7 @@ extern "C" grkan_status_t grkan_fwd(const void *x, const float *A, const float *
     grkan_plan_t pl;
     FwdArgs a;
     const void *kernel = nullptr;
-    st = plan_resident(rows, D, G, io, common_alignment({x, y}), info, dev, fwd_want(io), true, select_fwd, &pl,
+    st = plan_resident(rows, D, G, io, common_alignment({x, y}), info, dev, fwd_want(io), true, ops->fwd, &pl,
                        &a.walk, &kernel);
     if (st != GRKAN_OK)
         return st;
@@ -866,7 +980,8 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
                                     int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
                                     grkan_dtype_t io, void *hip_stream)
 {
-    grkan_status_t st = check_common(rows, D, G, m, n, io);
+    const DegreeOps *ops = nullptr;
+    grkan_status_t st = check_common(rows, D, G, m, n, io, &ops);
     if (st != GRKAN_OK)
         return st;
     if (!A || !B || !dA || !dB || (rows > 0 && (!x || !dy || !dx)))
@@ -884,11 +999,11 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
     grkan_plan_t pl;
     BwdArgs a;
     const void *kernel = nullptr;
-    st = plan_resident(rows, D, G, io, common_alignment({x, dy, dx}), info, dev, bwd_want(io), false, select_bwd, &pl,
+    st = plan_resident(rows, D, G, io, common_alignment({x, dy, dx}), info, dev, bwd_want(io), false, ops->bwd, &pl,
                        &a.walk, &kernel);
     if (st != GRKAN_OK)
         return st;
-    const size_t need = workspace_for(pl, G);
+    const size_t need = workspace_for(pl, G, m + 1 + n);
     if (need > 0 && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0))
         return GRKAN_ERR_WORKSPACE;
 
@@ -907,7 +1022,10 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
             return GRKAN_ERR_LAUNCH;
     }
     // with no rows there are no workspace rows and stage 2 writes zeros
-    hipLaunchKernelGGL(grkan_bwd_stage2_kernel, dim3(G), dim3(kStage2Threads), 0, stream, a.partial,
-                       pl.partials_per_group, dA, dB);
-    return hipGetLastError() == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
+    const float *partial = a.partial;
+    int32_t rows_per_group = pl.partials_per_group;
+    void *args2[] = {&partial, &rows_per_group, &dA, &dB};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(ops->stage2), dim3(G), dim3(kStage2Threads),
+                                         args2, 0, stream);
+    return e == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
 }

@@ -8,11 +8,11 @@
 
 namespace grkan {
 
-int elem_size(grkan_dtype_t io) { return io == GRKAN_F32 ? 4 : 2; }
+int elem_size(grkan_dtype_t io) { return io == GRKAN_F32 ? 4 : 2; } // bfloat16 and float16: 2
 
 grkan_status_t check_shape(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io)
 {
-    if (io != GRKAN_F32 && io != GRKAN_BF16)
+    if (io != GRKAN_F32 && io != GRKAN_BF16 && io != GRKAN_F16)
         return GRKAN_ERR_DTYPE;
     if (rows < 0 || D <= 0 || G <= 0 || D % G != 0)
         return GRKAN_ERR_SHAPE;

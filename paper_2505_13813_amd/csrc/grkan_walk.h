@@ -41,7 +41,7 @@
 namespace grkan {
 
 constexpr int kWave = 64;       // CDNA wavefront width
-constexpr int kNumCoef = 10;    // 6 numerator + 4 denominator coefficients
+constexpr int kMaxCoef = 14;    // most sums per group over the built degrees: (m, n) = (7, 6) -> m + 1 + n
 constexpr int kLineBytes = 128; // cache line the bundling rule is built around
 
 // Launch geometry in the form the kernels consume (all wave-uniform).

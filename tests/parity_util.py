@@ -19,11 +19,19 @@ from __future__ import annotations
 
 import numpy as np
 
-# fp32: tolerances of the target statement; bf16 I/O likewise
+# fp32: tolerances of the target statement; bf16 I/O likewise.  float16 I/O
+# (an addition of this library): y and dx are float32 results rounded once to 11
+# significant bits, half an ulp = 2^-11 = 4.9e-4 relative, so 1e-3; the sums see
+# the same float32 arithmetic as for bfloat16 I/O.
 TOL = {
     "f32": dict(y=1e-5, dx=1e-5, dA=1e-4, dB=1e-4),
     "bf16": dict(y=1e-2, dx=1e-2, dA=1e-3, dB=1e-3),
+    "f16": dict(y=1e-3, dx=1e-3, dA=1e-3, dB=1e-3),
 }
+# Below 2^-14 binary16 is subnormal, with a fixed spacing of 2^-24: rounding a
+# tiny y or dx to storage costs up to half of that in absolute terms, whatever
+# the size of the value.  (float32 and bfloat16 subnormals start at 1e-38.)
+ABS_FLOOR = {"f32": 0.0, "bf16": 0.0, "f16": 2.0 ** -25}
 
 
 def to_device(case, device="cuda:0"):
@@ -62,16 +70,18 @@ def run_oracle(oracle, case, threads=1, rows=None):
     return dict(y=y, dx=dx, dA=dA, dB=dB, Sy=Sy, Sdx=Sdx, RA=RA, RB=RB)
 
 
-def errors(gpu, ref, rows=None):
+def errors(gpu, ref, rows=None, dtype="f32"):
     sl = slice(None) if rows is None else rows
     tiny = np.finfo(np.float64).tiny
+    floor = ABS_FLOOR[dtype]
 
-    def rel(g, r, s):
+    def rel(g, r, s, floor=0.0):
         if r.size == 0:
             return 0.0
-        return float(np.max(np.abs(g - r) / np.maximum(np.maximum(np.abs(r), s), tiny)))
+        excess = np.maximum(np.abs(g - r) - floor, 0.0)
+        return float(np.max(excess / np.maximum(np.maximum(np.abs(r), s), tiny)))
 
-    out = dict(y=rel(gpu["y"][sl], ref["y"], ref["Sy"]), dx=rel(gpu["dx"][sl], ref["dx"], ref["Sdx"]))
+    out = dict(y=rel(gpu["y"][sl], ref["y"], ref["Sy"], floor), dx=rel(gpu["dx"][sl], ref["dx"], ref["Sdx"], floor))
     if "dA" in ref:
         out["dA"] = rel(gpu["dA"], ref["dA"], ref["RA"])
         out["dB"] = rel(gpu["dB"], ref["dB"], ref["RB"])
@@ -79,7 +89,7 @@ def errors(gpu, ref, rows=None):
 
 
 def assert_parity(gpu, ref, dtype, rows=None, what=("y", "dx", "dA", "dB"), label=""):
-    err = errors(gpu, ref, rows)
+    err = errors(gpu, ref, rows, dtype)
     for k in what:
         assert np.all(np.isfinite(gpu[k])), "%s: %s has non-finite values" % (label, k)
         assert err[k] <= TOL[dtype][k], "%s: %s error %.3e > %.1e" % (label, k, err[k], TOL[dtype][k])

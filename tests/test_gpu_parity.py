@@ -9,18 +9,20 @@ from parity_util import TOL, assert_parity, errors, run_gpu, run_oracle, to_devi
 pytestmark = pytest.mark.gpu
 
 
-def custom_case(seed, rows, D, G, dtype="f32", x_scale=1.0):
+def custom_case(seed, rows, D, G, dtype="f32", x_scale=1.0, m=5, n=4):
     rng = np.random.default_rng(seed)
-    A = (rng.uniform(-1, 1, size=(G, 6)) / (np.arange(6) + 1.0)).astype(np.float32)
-    B = rng.uniform(-0.5, 0.5, size=(G, 4)).astype(np.float32)
+    A = (rng.uniform(-1, 1, size=(G, m + 1)) / (np.arange(m + 1) + 1.0)).astype(np.float32)
+    B = rng.uniform(-0.5, 0.5, size=(G, n)).astype(np.float32)
     x = (rng.standard_normal((rows, D)) * x_scale).astype(np.float32)
     dy = rng.standard_normal((rows, D)).astype(np.float32)
-    case = dict(dtype=dtype, rows=rows, D=D, G=G, A=A, B=B, x=x, dy=dy)
-    if dtype == "bf16":
+    case = dict(dtype=dtype, rows=rows, D=D, G=G, m=m, n=n, A=A, B=B, x=x, dy=dy)
+    if dtype != "f32":
+        to_bits, widen = ((grkan_inputs.round_to_bf16_bits, grkan_inputs.bf16_bits_to_f32) if dtype == "bf16"
+                          else (grkan_inputs.round_to_f16_bits, grkan_inputs.f16_bits_to_f32))
         for k in ("x", "dy"):
-            bits = grkan_inputs.round_to_bf16_bits(case[k])
+            bits = to_bits(case[k])
             case[k + "_bits"] = bits
-            case[k] = grkan_inputs.bf16_bits_to_f32(bits)
+            case[k] = widen(bits)
     return case
 
 
@@ -30,13 +32,14 @@ def threads(oracle):
 
 
 # ------------------------------------------------------------------ config 0
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_tiny_config_elementwise(oracle, dtype):
-    case = grkan_inputs.make_case("tiny", dtype=dtype)
+@pytest.mark.parametrize("m,n", [(5, 4), (3, 2), (7, 6)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_tiny_config_elementwise(oracle, dtype, m, n):
+    case = grkan_inputs.make_case("tiny", dtype=dtype, m=m, n=n)
     gpu = run_gpu(case)
     ref = run_oracle(oracle, case)
-    err = assert_parity(gpu, ref, dtype, label="tiny/" + dtype)
-    print("tiny", dtype, err)
+    err = assert_parity(gpu, ref, dtype, label="tiny/%s (%d,%d)" % (dtype, m, n))
+    print("tiny", dtype, (m, n), err)
 
 
 # ------------------------------------------------------------------ shapes that span tiles, tails, vector widths
@@ -61,7 +64,7 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("rows,D,G", SHAPES)
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_shapes_elementwise(oracle, rows, D, G, dtype):
     case = custom_case(rows * 7919 + D * 31 + G, rows, D, G, dtype)
     gpu = run_gpu(case)
@@ -69,7 +72,17 @@ def test_shapes_elementwise(oracle, rows, D, G, dtype):
     assert_parity(gpu, ref, dtype, label="%dx%d G=%d %s" % (rows, D, G, dtype))
 
 
-@pytest.mark.parametrize("dtype,offset", [("f32", 1), ("f32", 2), ("bf16", 1), ("bf16", 2), ("bf16", 4)])
+@pytest.mark.parametrize("rows,D,G", SHAPES)
+@pytest.mark.parametrize("m,n,dtype", [(3, 2, "f32"), (3, 2, "bf16"), (7, 6, "f32"), (7, 6, "f16")])
+def test_shapes_elementwise_other_degrees(oracle, rows, D, G, m, n, dtype):
+    case = custom_case(rows * 7919 + D * 31 + G + 1000 * m, rows, D, G, dtype, m=m, n=n)
+    gpu = run_gpu(case)
+    ref = run_oracle(oracle, case, threads=4)
+    assert_parity(gpu, ref, dtype, label="%dx%d G=%d %s (%d,%d)" % (rows, D, G, dtype, m, n))
+
+
+@pytest.mark.parametrize("dtype,offset", [("f32", 1), ("f32", 2), ("bf16", 1), ("bf16", 2), ("bf16", 4),
+                                          ("f16", 1), ("f16", 2), ("f16", 4)])
 def test_misaligned_tensors_take_a_narrower_path(oracle, dtype, offset):
     import torch
 
@@ -180,7 +193,10 @@ def test_errors_from_the_device_side_checks():
         grkan.grkan_bwd(x, x, A, B, workspace=small)
     assert e.value.status == 5
     with pytest.raises(grkan.GrkanError) as e:
-        grkan.grkan_fwd(x, torch.zeros(8, 5, device="cuda:0"), B)
+        grkan.grkan_fwd(x, torch.zeros(8, 5, device="cuda:0"), B)  # (m, n) = (4, 4): not a built pair
+    assert e.value.status == 3
+    with pytest.raises(grkan.GrkanError) as e:
+        grkan.grkan_bwd(x, x, torch.zeros(8, 8, device="cuda:0"), B)  # (7, 4)
     assert e.value.status == 3
     with pytest.raises(grkan.GrkanError) as e:
         grkan.grkan_fwd(x, torch.zeros(7, 6, device="cuda:0"), torch.zeros(7, 4, device="cuda:0"))
@@ -188,7 +204,8 @@ def test_errors_from_the_device_side_checks():
 
 
 # ------------------------------------------------------------------ determinism
-@pytest.mark.parametrize("config,tensor,dtype", [("tiny", "x", "f32"), ("kat_b", "x2", "f32"), ("kat_b", "x1", "bf16")])
+@pytest.mark.parametrize("config,tensor,dtype", [("tiny", "x", "f32"), ("kat_b", "x2", "f32"), ("kat_b", "x1", "bf16"),
+                                                 ("kat_b", "x1", "f16")])
 def test_coefficient_gradients_are_bit_identical_run_to_run(config, tensor, dtype):
     import torch
 
@@ -200,7 +217,7 @@ def test_coefficient_gradients_are_bit_identical_run_to_run(config, tensor, dtyp
     for _ in range(4):
         dx, dA, dB = grkan.grkan_bwd(dev["x"], dev["dy"], dev["A"], dev["B"])
         torch.cuda.synchronize()
-        runs.append((dA.cpu().numpy().copy(), dB.cpu().numpy().copy(), dx.view(torch.int16 if dtype == "bf16" else torch.int32).cpu().numpy().copy()))
+        runs.append((dA.cpu().numpy().copy(), dB.cpu().numpy().copy(), dx.view(torch.int32 if dtype == "f32" else torch.int16).cpu().numpy().copy()))
     for dA, dB, dx in runs[1:]:
         assert np.array_equal(dA.view(np.uint32), runs[0][0].view(np.uint32))
         assert np.array_equal(dB.view(np.uint32), runs[0][1].view(np.uint32))
@@ -213,21 +230,24 @@ FULL = [
     ("kat_s", "x1", "f32", 8), ("kat_s", "x2", "f32", 8),
     ("kat_b", "x1", "f32", 8), ("kat_b", "x2", "f32", 8),
     ("kat_b", "x1", "bf16", 8), ("kat_b", "x2", "bf16", 8),
+    ("kat_b", "x1", "f16", 8), ("kat_b", "x2", "f16", 8),
     ("stress", "x", "f32", 1), ("stress", "x", "f32", 8), ("stress", "x", "f32", 64),
 ]
+# the neighbouring degree pairs at the headline shape
+FULL_DEGREES = [("kat_b", "x2", "f32", 8, 3, 2), ("kat_b", "x2", "f32", 8, 7, 6), ("kat_b", "x2", "bf16", 8, 7, 6)]
 
 _case_cache = {}
 
 
-def full_case(config, tensor, dtype, G):
+def full_case(config, tensor, dtype, G, m=5, n=4):
     key = (config, tensor, dtype)
     if key not in _case_cache:
         _case_cache.clear()
         _case_cache[key] = grkan_inputs.make_case(config, tensor, dtype=dtype)
     case = dict(_case_cache[key])
     cfg = grkan_inputs.CONFIGS[config]
-    case["A"], case["B"] = grkan_inputs.coefficients(cfg, G)
-    case["G"] = G
+    case["A"], case["B"] = grkan_inputs.coefficients(cfg, G, m, n)
+    case.update(G=G, m=m, n=n)
     return case
 
 
@@ -235,13 +255,22 @@ def full_case(config, tensor, dtype, G):
 def test_full_size_configuration(oracle, threads, config, tensor, dtype, G):
     """At the bench's sizes and launch configuration: dA / dB against the oracle
     over the whole array, y / dx on sampled rows (first, last, and random)."""
-    case = full_case(config, tensor, dtype, G)
+    check_full_size(oracle, threads, full_case(config, tensor, dtype, G))
+
+
+@pytest.mark.parametrize("config,tensor,dtype,G,m,n", FULL_DEGREES)
+def test_full_size_other_degrees(oracle, threads, config, tensor, dtype, G, m, n):
+    check_full_size(oracle, threads, full_case(config, tensor, dtype, G, m, n))
+
+
+def check_full_size(oracle, threads, case):
+    config, tensor, dtype, G = case["config"], case["tensor"], case["dtype"], case["G"]
     gpu = run_gpu(case)
     rows = case["rows"]
     rng = np.random.default_rng(99)
     pick = np.unique(np.concatenate([np.arange(0, 8), np.arange(rows - 8, rows), rng.integers(0, rows, 240)]))
     ref_s = run_oracle(oracle, case, threads=threads, rows=pick)
-    err = errors(gpu, dict(y=ref_s["y"], dx=ref_s["dx"], Sy=ref_s["Sy"], Sdx=ref_s["Sdx"]), rows=pick)
+    err = errors(gpu, dict(y=ref_s["y"], dx=ref_s["dx"], Sy=ref_s["Sy"], Sdx=ref_s["Sdx"]), rows=pick, dtype=dtype)
     assert err["y"] <= TOL[dtype]["y"], err
     assert err["dx"] <= TOL[dtype]["dx"], err
 
@@ -252,7 +281,8 @@ def test_full_size_configuration(oracle, threads, config, tensor, dtype, G):
     _, _, RA, RB = oracle.scales(x, dy, A, B, threads=threads)
     eA = float(np.max(np.abs(gpu["dA"] - dA) / np.maximum(np.abs(dA), RA)))
     eB = float(np.max(np.abs(gpu["dB"] - dB) / np.maximum(np.abs(dB), RB)))
-    print(config, tensor, dtype, "G=%d" % G, "y %.2e dx %.2e dA %.2e dB %.2e" % (err["y"], err["dx"], eA, eB))
+    print(config, tensor, dtype, "G=%d" % G, "(%d,%d)" % (case["m"], case["n"]),
+          "y %.2e dx %.2e dA %.2e dB %.2e" % (err["y"], err["dx"], eA, eB))
     assert np.all(np.isfinite(gpu["dA"])) and np.all(np.isfinite(gpu["dB"]))
     assert eA <= TOL[dtype]["dA"] and eB <= TOL[dtype]["dB"], (eA, eB)
     # plain relative error where the sums are well conditioned
@@ -335,7 +365,7 @@ def test_random_small_shapes_against_the_oracle(oracle):
     import paper_2505_13813_amd as grkan
 
     rng = random.Random(4242)
-    for trial in range(48):
+    for trial in range(96):
         G = rng.choice([1, 2, 3, 4, 5, 8, 16, 33])
         dg = rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 24, 31, 32, 48, 96, 100, 192, 384])
         rows = rng.choice([1, 2, 3, 17, 64, 65, 127, 301, 1000])
@@ -344,7 +374,12 @@ def test_random_small_shapes_against_the_oracle(oracle):
         D = G * dg
         if rows * D > 600_000:
             rows = max(1, 600_000 // D)
-        case = custom_case(100 + trial, rows, D, G, dtype)
+        # the second half of the sweep also draws the 16-bit float format and the other degree pairs
+        m, n = (5, 4)
+        if trial >= 48:
+            dtype = rng.choice(["f32", "bf16", "f16", "f16"])
+            m, n = rng.choice([(5, 4), (3, 2), (7, 6)])
+        case = custom_case(100 + trial, rows, D, G, dtype, m=m, n=n)
         dev = to_device(case)
         n = rows * D
 
@@ -363,4 +398,5 @@ def test_random_small_shapes_against_the_oracle(oracle):
         torch.cuda.synchronize()
         gpu = dict(y=to_host(y), dx=to_host(dx), dA=to_host(dA), dB=to_host(dB))
         ref = run_oracle(oracle, case)
-        assert_parity(gpu, ref, dtype, label="trial %d: %dx%d G=%d %s +%d" % (trial, rows, D, G, dtype, offset))
+        assert_parity(gpu, ref, dtype,
+                      label="trial %d: %dx%d G=%d %s (%d,%d) +%d" % (trial, rows, D, G, dtype, m, n, offset))

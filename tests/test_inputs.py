@@ -69,4 +69,32 @@ def test_bad_requests():
     with pytest.raises(ValueError):
         gi.make_case("tiny", G=7)
     with pytest.raises(ValueError):
-        gi.make_case("tiny", dtype="f16")
+        gi.make_case("tiny", dtype="f64")
+
+
+def test_f16_rounding_is_nearest_even_and_exactly_widened():
+    # 1 + 2^-11 lies halfway between 1 and the next binary16 value 1 + 2^-10: ties go to the even one
+    f = np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -11 + 2.0 ** -20, 65504.0, 2.0 ** -24],
+                 dtype=np.float32)
+    back = gi.f16_bits_to_f32(gi.round_to_f16_bits(f))
+    assert back.tolist() == [1.0, 1.0 + 2.0 ** -9, 1.0 + 2.0 ** -10, 65504.0, 2.0 ** -24]
+    c = gi.make_case("kat_b", "x1", dtype="f16", rows=4)
+    assert c["x_bits"].dtype == np.uint16
+    assert np.array_equal(gi.f16_bits_to_f32(c["x_bits"]), c["x"])
+    assert np.array_equal(gi.round_to_f16_bits(c["x"]), c["x_bits"])
+    # same draws as the float32 case, rounded once
+    c32 = gi.make_case("kat_b", "x1", dtype="f32", rows=4)
+    assert np.max(np.abs(c["x"] - c32["x"]) / np.maximum(np.abs(c32["x"]), 2.0 ** -14)) <= 2.0 ** -11
+
+
+def test_other_degrees_reuse_the_coefficient_streams():
+    cfg = gi.CONFIGS["tiny"]
+    A54, B54 = gi.coefficients(cfg)
+    A32, B32 = gi.coefficients(cfg, m=3, n=2)
+    A76, B76 = gi.coefficients(cfg, m=7, n=6)
+    assert A32.shape == (8, 4) and B32.shape == (8, 2) and A76.shape == (8, 8) and B76.shape == (8, 6)
+    assert np.all(np.abs(A76) <= 1.0 / (np.arange(8) + 1.0)) and np.all(np.abs(B76) <= 0.5)
+    c = gi.make_case("tiny", m=7, n=6)
+    assert (c["m"], c["n"]) == (7, 6) and np.array_equal(c["A"], A76)
+    # x and dy do not depend on the degrees
+    assert np.array_equal(c["x"], gi.make_case("tiny")["x"])
