@@ -32,9 +32,13 @@ sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: 256 CUs x 64 lanes x 2.4 GHz, unpacked float32
-# Vector-ALU issue slots per element of the backward loop for 16-bit I/O (instructions counted in
-# the ISA and confirmed with the SQ_INSTS_VALU counter; the quarter-rate reciprocal counts as 4).
-BWD_VALU_SLOTS_16BIT = {("bf16", 5, 4): 49}
+# Vector-ALU instructions the backward stage-1 kernel issues per element with 16-bit I/O, measured with the
+# SQ_INSTS_VALU counter at the KAT-B x2 shape (wave instructions x 64 lanes / elements; the summary is under
+# profiles/).  Every instruction is priced as one issue slot, the reciprocal included.
+BWD_VALU_INSTR_16BIT = {
+    ("bf16", 3, 2): 33.00, ("bf16", 5, 4): 47.26, ("bf16", 7, 6): 61.43,
+    ("f16", 3, 2): 33.97, ("f16", 5, 4): 48.08, ("f16", 7, 6): 62.19,
+}
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); the
@@ -264,7 +268,7 @@ def main():
     key = "%s/%s/bwd_%s" % (args.workload, args.dtype, dom_name)
     if (m_deg, n_deg) != (5, 4):
         key += "/%d,%d" % (m_deg, n_deg)
-    slots = BWD_VALU_SLOTS_16BIT.get((args.dtype, m_deg, n_deg))
+    slots = BWD_VALU_INSTR_16BIT.get((args.dtype, m_deg, n_deg))
     what = "grkan_bwd on %s [%d,%d] (stage 1 + stage 2)" % (dom_name, dom.rows, dom.D)
     if args.dtype == "f32" or slots is None:
         achieved = dom.bwd_bytes() / (dom_ms * 1e-3) / 1e9
@@ -281,7 +285,7 @@ def main():
         roofline = {
             "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TOPS, "unit": "T lane-op/s",
             "frac": achieved / VALU_PEAK_TOPS, "traffic": None,
-            "kernel": "%s, %d vector-ALU issue slots per element x %d elements per launch, avg %.2f us "
+            "kernel": "%s, %.2f vector-ALU instructions per element x %d elements per launch, avg %.2f us "
                       "(HBM side: %.0f GB/s)" % (what, slots, dom.M, dom_ms * 1e3,
                                                   dom.bwd_bytes() / (dom_ms * 1e-3) / 1e9),
         }
