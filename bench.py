@@ -365,7 +365,7 @@ def main():
 
     block = None
     if args.mlp_block:
-        # context for the paper's "FlashKAT is still about 25 % slower than a standard Transformer"
+        # context for the paper's closing remark that FlashKAT remains roughly a quarter slower than a standard Transformer
         from paper_2505_13813_amd import nn as gnn
 
         block = {}

@@ -26,7 +26,7 @@ Recipe (fixed, so every consumer sees the same arrays):
   * other degrees (m, n): the same two child streams with the shapes
     [G, m + 1] / [G, n] and the same scaling 1 / (i + 1)
   * a sweep over G redraws A and B from the same two child streams with the
-    new shape [G, 6] / [G, 4]; x and dy do not depend on G.
+    new shape [G, m + 1] / [G, n]; x and dy do not depend on G.
 """
 from __future__ import annotations
 

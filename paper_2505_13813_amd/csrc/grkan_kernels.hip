@@ -7,14 +7,15 @@
 // block; here there are no atomics at all:
 //
 //   stage 1  Each lane streams 128-bit vectors of x and dy, writes dx, and
-//            keeps the ten partial sums in registers for the whole kernel.
+//            keeps the m + 1 + n partial sums (ten for the paper's degrees) in
+//            registers for the whole kernel.
 //            Group walk (long, line-aligned group segments): one wavefront =
 //            one group, coefficients in scalar registers; the wavefront folds
 //            its sums with DPP row/bank operations, the workgroup folds its
 //            wavefronts through LDS.  Flat walk (short segments): wavefronts
 //            read whole rows, each lane holds the coefficients of its fixed
 //            column's group, and the workgroup folds lanes -> runs -> groups
-//            through LDS.  Either way one row of ten floats per (workgroup,
+//            through LDS.  Either way one row of m + 1 + n floats per (workgroup,
 //            group) goes to a workspace.
 //   stage 2  one wavefront per group adds that group's workspace rows in a
 //            fixed order (in double) and overwrites dA / dB.
@@ -372,7 +373,7 @@ struct BwdArgs {
     char *dx;
     const float *A;
     const float *B;
-    float *partial; // [G][rows_per_group][10]
+    float *partial; // [G][rows_per_group][m + 1 + n]
     int32_t Gc;     // coefficient groups
     int32_t dgc;    // channels per coefficient group (differs from walk.dg in the flat walk)
     Walk walk;
@@ -594,7 +595,7 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
 }
 
 // Stage 2.  One wavefront per group: lane l adds the group's workspace rows
-// l, l + 64, ... in double, the 64 lane sums go through LDS, and ten lanes add
+// l, l + 64, ... in double, the 64 lane sums go through LDS, and m + 1 + n lanes add
 // them in lane order.  Every order is fixed; dA / dB are overwritten.
 constexpr int kStage2Threads = kWave;
 

@@ -275,7 +275,7 @@ extern "C" const char *grkan_status_string(grkan_status_t s)
     case GRKAN_OK: return "ok";
     case GRKAN_ERR_NULL: return "null pointer";
     case GRKAN_ERR_SHAPE: return "bad shape (need rows >= 0, D > 0, G > 0, D % G == 0)";
-    case GRKAN_ERR_DEGREE: return "unsupported degrees (only m = 5, n = 4 are built)";
+    case GRKAN_ERR_DEGREE: return "unsupported degrees (built: (m, n) = (5, 4), (3, 2), (7, 6))";
     case GRKAN_ERR_ALIGN: return "pointer not aligned to its element size";
     case GRKAN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case GRKAN_ERR_DTYPE: return "unknown dtype";

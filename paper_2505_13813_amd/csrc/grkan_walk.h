@@ -4,7 +4,7 @@
 // channel c uses the coefficients of group c div d_g).  Group g owns a slab of
 // rows x d_g elements, seen as rows * v vectors of `vec` elements
 // (v = d_g / vec), numbered t = row * v + col.  A wavefront is bound to one
-// group for the whole kernel, so the coefficients are wave-uniform and the ten
+// group for the whole kernel, so the coefficients are wave-uniform and the m + 1 + n
 // coefficient-gradient partial sums can be reduced across the wavefront
 // without regard to group boundaries.  Wave w of the Wg waves of a group visits
 // the 64-vector chunks w, w + Wg, w + 2 Wg, ... of that numbering.

@@ -6,9 +6,9 @@ Only the rational function runs in this package's kernels; the matrix products
 are torch's (library GEMMs).  Conventions taken from the FlashKAT paper:
   * GR-KAN(x) = W F(x): the rational function is applied to the INPUT of each
     linear layer (Eq. "GR_KAN").
-  * "each of the 8 groups shares its 6 numerator coefficients and has 4 unique
-    denominator coefficients" (Sec. "Results"): one numerator row, broadcast to
-    the kernel's [G, 6] layout; autograd's expand sums dA over the groups.
+  * the groups use one common set of numerator coefficients and have their own
+    denominator coefficients (Sec. "Results"): one numerator row, broadcast to
+    the kernel's [G, m+1] layout; autograd's expand sums dA over the groups.
   * the first rational of an MLP block starts as the identity, the second as a
     Swish (Sec. "Results").  The paper prints no Swish coefficients, so they
     are obtained here by a (linearised) least-squares fit on [-3, 3].
@@ -54,7 +54,7 @@ class GroupRationalFunction(torch.autograd.Function):
 
 
 def group_rational(x, A, B):
-    """Functional form: x [..., D] float32/bfloat16 on the GPU, A [G, 6], B [G, 4] float32."""
+    """Functional form: x [..., D] float32 / bfloat16 / float16 on the GPU, A [G, m+1], B [G, n] float32."""
     return GroupRationalFunction.apply(x, A, B)
 
 
@@ -65,21 +65,22 @@ def _rational_np(x, a, b):
 
 
 @lru_cache(maxsize=None)
-def swish_coefficients() -> Tuple[Tuple[float, ...], Tuple[float, ...]]:
-    """(a_0..a_5, b_1..b_4) of a safe Pade unit fitted to Swish, x * sigmoid(x).
+def swish_coefficients(m: int = M_DEGREE, n: int = N_DEGREE) -> Tuple[Tuple[float, ...], Tuple[float, ...]]:
+    """(a_0..a_m, b_1..b_n) of a safe Pade unit fitted to Swish, x * sigmoid(x).
 
     Linearised least squares on a uniform grid over [-3, 3]: minimise
     |P(x) - t(x) * sum_j b_j x^j - t(x)| over (a, b), which is linear.  The
-    solution has an even, non-negative denominator polynomial
-    (b_1 = b_3 = 0, b_2, b_4 > 0), so the absolute value of the safe unit is
-    inactive and the fit error of F itself is below 1e-6 on the grid (8e-3 on
-    [-6, 6]).  Deterministic: plain linear algebra in float64.
+    solution has an even, non-negative denominator polynomial (odd b_j = 0,
+    even b_j > 0), so the absolute value of the safe unit is inactive; for
+    (5, 4) the fit error of F itself is below 1e-6 on the grid (8e-3 on
+    [-6, 6]), for (3, 2) 5e-3, for (7, 6) 1e-10.  Deterministic: plain linear
+    algebra in float64.
     """
     xs = np.linspace(-3.0, 3.0, 601)
     target = xs / (1.0 + np.exp(-xs))
-    cols = [xs ** i for i in range(M_DEGREE + 1)] + [-target * xs ** (j + 1) for j in range(N_DEGREE)]
+    cols = [xs ** i for i in range(m + 1)] + [-target * xs ** (j + 1) for j in range(n)]
     theta, *_ = np.linalg.lstsq(np.stack(cols, axis=1), target, rcond=None)
-    return tuple(float(v) for v in theta[:M_DEGREE + 1]), tuple(float(v) for v in theta[M_DEGREE + 1:])
+    return tuple(float(v) for v in theta[:m + 1]), tuple(float(v) for v in theta[m + 1:])
 
 
 def second_moment(a, b, points: int = 128) -> float:
@@ -94,15 +95,21 @@ class GroupRational(nn.Module):
 
     `init`: "identity" (a = e_1, b = 0) or "swish".  With `shared_numerator`
     (the paper's setting) there is one numerator row for all groups.
+    `degrees` = (m, n), one of the pairs the library is built for.
     """
 
-    def __init__(self, groups: int = 8, init: str = "identity", shared_numerator: bool = True):
+    def __init__(self, groups: int = 8, init: str = "identity", shared_numerator: bool = True,
+                 degrees: Tuple[int, int] = (M_DEGREE, N_DEGREE)):
         super().__init__()
+        m, n = (int(v) for v in degrees)
+        if (m, n) not in binding.DEGREES:
+            raise ValueError("degrees must be one of %s" % (binding.DEGREES,))
+        self.degrees = (m, n)
         if init == "identity":
-            a = [0.0, 1.0] + [0.0] * (M_DEGREE - 1)
-            b = [0.0] * N_DEGREE
+            a = [0.0, 1.0] + [0.0] * (m - 1)
+            b = [0.0] * n
         elif init == "swish":
-            a, b = swish_coefficients()
+            a, b = swish_coefficients(m, n)
         else:
             raise ValueError("init must be 'identity' or 'swish'")
         self.groups = int(groups)
@@ -113,7 +120,7 @@ class GroupRational(nn.Module):
         self.denominator = nn.Parameter(b_t.repeat(self.groups, 1))
 
     def coefficient_rows(self):
-        A = self.numerator.expand(self.groups, M_DEGREE + 1) if self.shared_numerator else self.numerator
+        A = self.numerator.expand(self.groups, self.degrees[0] + 1) if self.shared_numerator else self.numerator
         return A, self.denominator
 
     def second_moment(self) -> float:
@@ -132,11 +139,12 @@ class GRKANLinear(nn.Module):
     """GR-KAN(x) = W F(x) + bias (Eq. "GR_KAN"), variance-preserving init."""
 
     def __init__(self, in_features: int, out_features: int, groups: int = 8, init: str = "identity",
-                 bias: bool = True, shared_numerator: bool = True):
+                 bias: bool = True, shared_numerator: bool = True,
+                 degrees: Tuple[int, int] = (M_DEGREE, N_DEGREE)):
         super().__init__()
         if in_features % groups:
             raise ValueError("in_features must be a multiple of groups")
-        self.rational = GroupRational(groups, init, shared_numerator)
+        self.rational = GroupRational(groups, init, shared_numerator, degrees)
         self.linear = nn.Linear(in_features, out_features, bias=bias)
         alpha = 1.0 / self.rational.second_moment()  # Var[x] / E[F(x)^2] with Var[x] = 1
         with torch.no_grad():
@@ -152,11 +160,12 @@ class KATMlp(nn.Module):
     """The MLP of a KAT block: two GR-KAN layers, hidden width 4x by default;
     the first rational starts as the identity, the second as Swish."""
 
-    def __init__(self, dim: int, hidden: int | None = None, groups: int = 8):
+    def __init__(self, dim: int, hidden: int | None = None, groups: int = 8,
+                 degrees: Tuple[int, int] = (M_DEGREE, N_DEGREE)):
         super().__init__()
         hidden = 4 * dim if hidden is None else hidden
-        self.fc1 = GRKANLinear(dim, hidden, groups, init="identity")
-        self.fc2 = GRKANLinear(hidden, dim, groups, init="swish")
+        self.fc1 = GRKANLinear(dim, hidden, groups, init="identity", degrees=degrees)
+        self.fc2 = GRKANLinear(hidden, dim, groups, init="swish", degrees=degrees)
 
     def forward(self, x):
         return self.fc2(self.fc1(x))

@@ -24,6 +24,21 @@ def test_swish_fit_is_tight_and_uses_a_positive_denominator():
     assert aden.min() > -1e-9  # |.| never active: F is smooth
 
 
+@pytest.mark.parametrize("m,n,tol", [(3, 2, 6e-3), (7, 6, 1e-8)])
+def test_swish_fit_for_the_other_degree_pairs(m, n, tol):
+    a, b = gnn.swish_coefficients(m, n)
+    assert len(a) == m + 1 and len(b) == n
+    xs = np.linspace(-3, 3, 997)
+    assert np.abs(gnn._rational_np(xs, np.array(a), np.array(b)) - swish(xs)).max() < tol
+    aden = sum(b[j] * xs ** (j + 1) for j in range(n))
+    assert aden.min() > -1e-9
+    layer = gnn.GroupRational(4, init="swish", degrees=(m, n))
+    A, B = layer.coefficient_rows()
+    assert A.shape == (4, m + 1) and B.shape == (4, n)
+    with pytest.raises(ValueError):
+        gnn.GroupRational(4, degrees=(4, 4))
+
+
 def test_second_moment_matches_closed_forms():
     # identity: E[x^2] = 1; x^2: E[x^4] = 3; Swish fit: E[swish^2] by direct quadrature
     assert abs(gnn.second_moment([0, 1, 0, 0, 0, 0], [0, 0, 0, 0]) - 1.0) < 1e-12
