@@ -101,3 +101,22 @@ def test_rounding_error_of_coefficient_gradients_vs_alg1(oracle):
     # the deterministic reduction is the more accurate one, by a wide margin (the paper reports ~100x;
     # measured here: ~100x on dA, 70-120x on dB)
     assert ours[0, 0] * 10 < alg1[:, 0].mean() and ours[0, 1] * 10 < alg1[:, 1].mean()
+
+    # The appendix closes with the remark that the smaller rounding error should matter most for
+    # low-precision training.  The same experiment with 16-bit activations and upstream gradients
+    # (rounded inputs on both sides, fp64 oracle on those): the sums never leave float32 registers, so
+    # the coefficient gradients keep float32-level accuracy whatever the storage format.
+    for dtype, to_bits, widen in (("bf16", grkan_inputs.round_to_bf16_bits, grkan_inputs.bf16_bits_to_f32),
+                                  ("f16", grkan_inputs.round_to_f16_bits, grkan_inputs.f16_bits_to_f32)):
+        xb, dyb = to_bits(x), to_bits(dy)
+        low = dict(dtype=dtype, A=A, B=B, x=widen(xb), dy=widen(dyb), x_bits=xb, dy_bits=dyb)
+        _, dA_low, dB_low = oracle.bwd(low["x"].astype(np.float64), low["dy"].astype(np.float64),
+                                       A.astype(np.float64), B.astype(np.float64), threads=threads)
+        dlow = to_device(low)
+        _, dA_g, dB_g = grkan.grkan_bwd(dlow["x"], dlow["dy"], dlow["A"], dlow["B"])
+        torch.cuda.synchronize()
+        mA = float(np.mean(np.abs(to_host(dA_g) - dA_low)))
+        mB = float(np.mean(np.abs(to_host(dB_g) - dB_low)))
+        print("  grkan_bwd, %s I/O, float32 sums: dA MAE %.3e (%.1e of mean |dA|) | dB MAE %.3e (%.1e of mean |dB|)" %
+              (dtype, mA, mA / np.mean(np.abs(dA_low)), mB, mB / np.mean(np.abs(dB_low))))
+        assert mA <= 1e-4 * np.mean(np.abs(dA_low)) and mB <= 1e-4 * np.mean(np.abs(dB_low))
