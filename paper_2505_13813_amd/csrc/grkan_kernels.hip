@@ -594,40 +594,58 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
     }
 }
 
-// Stage 2.  One wavefront per group: lane l adds the group's workspace rows
-// l, l + 64, ... in double, the 64 lane sums go through LDS, and m + 1 + n lanes add
-// them in lane order.  Every order is fixed; dA / dB are overwritten.
-constexpr int kStage2Threads = kWave;
+// Stage 2.  One workgroup per group, of one wavefront when the group has at
+// most 64 workspace rows and of four otherwise (the flat walk leaves one row
+// per stage-1 workgroup; reading hundreds of rows with 64 lanes is a chain of
+// dependent memory latencies).  Thread t adds rows t, t + T, ... in double; the
+// T thread sums go through LDS, each block of 64 of them is added in thread
+// order, then the blocks in block order.  Every order is fixed by T and the row
+// count; dA / dB are overwritten.
+constexpr int kStage2MaxThreads = 4 * kWave;
+
+static int stage2_threads(int32_t rows_per_group) { return rows_per_group > kWave ? kStage2MaxThreads : kWave; }
 
 template <int M, int N>
-__global__ __launch_bounds__(kStage2Threads) void grkan_bwd_stage2_kernel(const float *__restrict__ partial,
-                                                                          int32_t rows_per_group,
-                                                                          float *__restrict__ dA,
-                                                                          float *__restrict__ dB)
+__global__ __launch_bounds__(kStage2MaxThreads) void grkan_bwd_stage2_kernel(const float *__restrict__ partial,
+                                                                             int32_t rows_per_group,
+                                                                             float *__restrict__ dA,
+                                                                             float *__restrict__ dB)
 {
     constexpr int kNumCoef = M + 1 + N;
-    __shared__ double lane_sum[kNumCoef][kStage2Threads];
+    constexpr int kBlocks = kStage2MaxThreads / kWave;
+    __shared__ double thread_sum[kNumCoef][kStage2MaxThreads];
+    __shared__ double block_sum[kNumCoef][kBlocks];
     const int g = blockIdx.x;
     const int tid = threadIdx.x;
+    const int T = blockDim.x; // 64 or 256
     const float *base = partial + (size_t)g * rows_per_group * kNumCoef;
 
     double s[kNumCoef];
 #pragma unroll
     for (int k = 0; k < kNumCoef; ++k)
         s[k] = 0.0;
-    for (int r = tid; r < rows_per_group; r += kStage2Threads) {
+    for (int r = tid; r < rows_per_group; r += T) {
 #pragma unroll
         for (int k = 0; k < kNumCoef; ++k)
             s[k] += (double)base[(size_t)r * kNumCoef + k];
     }
 #pragma unroll
     for (int k = 0; k < kNumCoef; ++k)
-        lane_sum[k][tid] = s[k];
+        thread_sum[k][tid] = s[k];
+    __syncthreads();
+    const int nblocks = T / kWave;
+    if (tid < kNumCoef * nblocks) {
+        const int k = tid / nblocks, b = tid - k * nblocks;
+        double t = 0.0;
+        for (int l = 0; l < kWave; ++l)
+            t += thread_sum[k][b * kWave + l];
+        block_sum[k][b] = t;
+    }
     __syncthreads();
     if (tid < kNumCoef) {
         double t = 0.0;
-        for (int l = 0; l < kStage2Threads; ++l)
-            t += lane_sum[tid][l];
+        for (int b = 0; b < nblocks; ++b)
+            t += block_sum[tid][b];
         if (tid <= M)
             dA[g * (M + 1) + tid] = (float)t;
         else
@@ -1026,7 +1044,7 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
     const float *partial = a.partial;
     int32_t rows_per_group = pl.partials_per_group;
     void *args2[] = {&partial, &rows_per_group, &dA, &dB};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(ops->stage2), dim3(G), dim3(kStage2Threads),
-                                         args2, 0, stream);
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(ops->stage2), dim3(G),
+                                         dim3(stage2_threads(rows_per_group)), args2, 0, stream);
     return e == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
 }
