@@ -185,6 +185,17 @@ __device__ __forceinline__ float bwd_elem(float x, float d, const Coef<M, N> &c,
 typedef const __attribute__((address_space(1))) char *gcptr_t;
 typedef __attribute__((address_space(1))) char *gptr_t;
 
+// Marks a lane value as redefined at this point (no instruction is emitted).  Used on the 32-bit lane
+// offset at the top of the streaming loops: its zero-extension then stays inside the loop body, where
+// the address "scalar base + 32-bit lane offset" is recognised as such; hoisted out of the loop it would
+// become a 64-bit lane value and every access would pay a 64-bit vector addition.
+__device__ __forceinline__ void keep_in_loop(uint32_t &v) { asm volatile("" : "+v"(v)); }
+
+// The instruction scheduler may not move anything across this point.  Placed after the prefetch loads:
+// left alone, the scheduler sinks them into the arithmetic of the chunk before (dozens of instructions
+// later), which shortens the time they have to arrive.
+__device__ __forceinline__ void issue_before_what_follows() { __builtin_amdgcn_sched_barrier(0); }
+
 __device__ __forceinline__ uint64_t uniform_u64(uint64_t v)
 {
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
@@ -227,6 +238,9 @@ template <typename IO> __device__ __forceinline__ void widen_pair(uint32_t w, fl
         const f16x2 h = __builtin_bit_cast(f16x2, w);
         lo = (float)h[0];
         hi = (float)h[1];
+        // keep the two conversions as instructions of their own: folded into mixed-precision FMAs
+        // (one per use of x) they cost the backward kernel registers and time
+        asm volatile("" : "+v"(lo), "+v"(hi));
     }
 }
 
@@ -281,6 +295,14 @@ template <typename IO, int VEC> __device__ __forceinline__ RawT<IO, VEC> load_ra
 {
     using Raw = RawT<IO, VEC>;
     return __builtin_nontemporal_load((const __attribute__((address_space(1))) Raw *)p);
+}
+
+// Reads a loaded vector at this point (no instruction is emitted), so that the wait for its load is
+// placed here and not at its first real use further down.
+template <typename IO, int VEC> __device__ __forceinline__ void arrived(const RawT<IO, VEC> &r)
+{
+    const uint32_t w = raw_word<(int)sizeof(IO) * VEC>(r, 0);
+    asm volatile("" : : "v"(w));
 }
 
 template <typename IO, int VEC> __device__ __forceinline__ void unpack(const RawT<IO, VEC> &r, float (&out)[VEC])
@@ -416,26 +438,47 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
     if constexpr (FIXED) {
         const uint64_t base0 = (uint64_t)(fixed_base0(p, id.g, id.w) * ES);
         const uint64_t step = (uint64_t)(fixed_step(p) * ES);
-        const uint32_t lo = fixed_lane_offset(p, id.w, lane) * (uint32_t)ES;
+        uint32_t lo = fixed_lane_offset(p, id.w, lane) * (uint32_t)ES;
         // chunk `i` of this wave: scalar base + lane offset
         auto xin = [&](int32_t i) { return (gcptr_t)uniform_u64(x0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
         auto yout = [&](int32_t i) { return (gptr_t)uniform_u64(y0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
 
-        float xs[VEC];
-        if (n_it > 0)
-            load_vec<IO, VEC>(xin(0), xs);
-        for (int32_t it = 0; it < n_it; ++it) {
-            const bool more = it + 1 < n_it;
-            RawT<IO, VEC> xn{};
-            if (more)
-                xn = load_raw<IO, VEC>(xin(it + 1)); // prefetch: raw, untouched until after the arithmetic
-            float yv[VEC];
+        // chunk i: raw bits in, results out
+        auto work = [&](const RawT<IO, VEC> &rx, int32_t i) {
+            float xs[VEC], yv[VEC];
+            unpack<IO, VEC>(rx, xs);
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
                 yv[e] = fwd_elem<WIDE, M, N>(xs[e], c);
-            store_vec<IO, VEC>(yout(it), yv);
-            if (more)
-                unpack<IO, VEC>(xn, xs); // the wait for the prefetch lands here
+            store_vec<IO, VEC>(yout(i), yv);
+        };
+        if (n_it > 0) {
+            // Two register sets take turns, so nothing is copied from "next" to "current" and the loop
+            // body has no conditional load.  Per half trip: issue the loads of the following chunk
+            // (raw, untouched), work on the current one, then wait for those loads before issuing any
+            // more - one chunk of loads in flight per wave, which is what the persistent grid is sized for.
+            RawT<IO, VEC> ra = load_raw<IO, VEC>(xin(0));
+            arrived<IO, VEC>(ra); // the loop is entered, like re-entered, with nothing to wait for
+            int32_t it = 0;
+            for (; it + 2 < n_it; it += 2) {
+                keep_in_loop(lo);
+                const RawT<IO, VEC> rb = load_raw<IO, VEC>(xin(it + 1));
+                issue_before_what_follows();
+                work(ra, it);
+                arrived<IO, VEC>(rb);
+                ra = load_raw<IO, VEC>(xin(it + 2));
+                issue_before_what_follows();
+                work(rb, it + 1);
+                arrived<IO, VEC>(ra);
+            }
+            if (it + 1 < n_it) {
+                const RawT<IO, VEC> rb = load_raw<IO, VEC>(xin(it + 1));
+                issue_before_what_follows();
+                work(ra, it);
+                work(rb, it + 1);
+            } else {
+                work(ra, it);
+            }
         }
         if (tail)
             one(base0 + (uint64_t)(uint32_t)n_it * step + lo);
@@ -488,32 +531,55 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
     if constexpr (FIXED) {
         const uint64_t base0 = (uint64_t)(fixed_base0(p, id.g, id.w) * ES);
         const uint64_t step = (uint64_t)(fixed_step(p) * ES);
-        const uint32_t lo = fixed_lane_offset(p, id.w, lane) * (uint32_t)ES;
+        uint32_t lo = fixed_lane_offset(p, id.w, lane) * (uint32_t)ES;
         // chunk `i` of this wave: scalar base + lane offset
         auto xin = [&](int32_t i) { return (gcptr_t)uniform_u64(x0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
         auto dyin = [&](int32_t i) { return (gcptr_t)uniform_u64(dy0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
         auto dxout = [&](int32_t i) { return (gptr_t)uniform_u64(dx0 + base0 + (uint64_t)(uint32_t)i * step) + lo; };
 
-        float xs[VEC], ds[VEC];
-        if (n_it > 0) {
-            load_vec<IO, VEC>(xin(0), xs);
-            load_vec<IO, VEC>(dyin(0), ds);
-        }
-        for (int32_t it = 0; it < n_it; ++it) {
-            const bool more = it + 1 < n_it;
-            RawT<IO, VEC> xn{}, dn{};
-            if (more) { // prefetch the next chunk: raw, untouched until after the arithmetic
-                xn = load_raw<IO, VEC>(xin(it + 1));
-                dn = load_raw<IO, VEC>(dyin(it + 1));
-            }
-            float ov[VEC];
+        // chunk i: raw bits in, dx out, sums updated
+        auto work = [&](const RawT<IO, VEC> &rx, const RawT<IO, VEC> &rd, int32_t i) {
+            float xs[VEC], ds[VEC], ov[VEC];
+            unpack<IO, VEC>(rx, xs);
+            unpack<IO, VEC>(rd, ds);
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
                 ov[e] = bwd_elem<WIDE, M, N>(xs[e], ds[e], c, acc);
-            store_vec<IO, VEC>(dxout(it), ov);
-            if (more) { // the wait for the prefetch lands here
-                unpack<IO, VEC>(xn, xs);
-                unpack<IO, VEC>(dn, ds);
+            store_vec<IO, VEC>(dxout(i), ov);
+        };
+        if (n_it > 0) {
+            // Two register sets take turns, so nothing is copied from "next" to "current" and the loop
+            // body has no conditional load.  Per half trip: issue the loads of the following chunk
+            // (raw, untouched), work on the current one, then wait for those loads before issuing any
+            // more - one chunk of loads in flight per wave, which is what the persistent grid is sized for.
+            RawT<IO, VEC> xa = load_raw<IO, VEC>(xin(0));
+            RawT<IO, VEC> da = load_raw<IO, VEC>(dyin(0));
+            arrived<IO, VEC>(xa); // the loop is entered, like re-entered, with nothing to wait for
+            arrived<IO, VEC>(da);
+            int32_t it = 0;
+            for (; it + 2 < n_it; it += 2) {
+                keep_in_loop(lo);
+                const RawT<IO, VEC> xb = load_raw<IO, VEC>(xin(it + 1));
+                const RawT<IO, VEC> db = load_raw<IO, VEC>(dyin(it + 1));
+                issue_before_what_follows();
+                work(xa, da, it);
+                arrived<IO, VEC>(xb);
+                arrived<IO, VEC>(db);
+                xa = load_raw<IO, VEC>(xin(it + 2));
+                da = load_raw<IO, VEC>(dyin(it + 2));
+                issue_before_what_follows();
+                work(xb, db, it + 1);
+                arrived<IO, VEC>(xa);
+                arrived<IO, VEC>(da);
+            }
+            if (it + 1 < n_it) {
+                const RawT<IO, VEC> xb = load_raw<IO, VEC>(xin(it + 1));
+                const RawT<IO, VEC> db = load_raw<IO, VEC>(dyin(it + 1));
+                issue_before_what_follows();
+                work(xa, da, it);
+                work(xb, db, it + 1);
+            } else {
+                work(xa, da, it);
             }
         }
         if (tail)
