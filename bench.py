@@ -36,8 +36,8 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: 256 CUs x 
 # SQ_INSTS_VALU counter at the KAT-B x2 shape (wave instructions x 64 lanes / elements; the summary is under
 # profiles/).  Every instruction is priced as one issue slot, the reciprocal included.
 BWD_VALU_INSTR_16BIT = {
-    ("bf16", 3, 2): 33.00, ("bf16", 5, 4): 47.26, ("bf16", 7, 6): 61.43,
-    ("f16", 3, 2): 33.97, ("f16", 5, 4): 48.08, ("f16", 7, 6): 62.19,
+    ("bf16", 3, 2): 30.46, ("bf16", 5, 4): 44.90, ("bf16", 7, 6): 58.67,
+    ("f16", 3, 2): 30.52, ("f16", 5, 4): 44.77, ("f16", 7, 6): 58.93,
 }
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
@@ -45,7 +45,7 @@ BWD_VALU_INSTR_16BIT = {
 # summaries are under profiles/.  None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/bench_kat_b_f32_hbm_traffic.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB, stage 1 + stage 2
-    "kat_b/f32/bwd_x2": 907937 * 1024,
+    "kat_b/f32/bwd_x2": 908021 * 1024,
 }
 
 
