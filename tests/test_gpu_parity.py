@@ -81,6 +81,25 @@ def test_shapes_elementwise_other_degrees(oracle, rows, D, G, m, n, dtype):
     assert_parity(gpu, ref, dtype, label="%dx%d G=%d %s (%d,%d)" % (rows, D, G, dtype, m, n))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("D,G", [(768, 8), (192, 8)])  # group walk / flat walk
+def test_every_trip_count_of_the_streaming_loop(oracle, monkeypatch, dtype, D, G):
+    """The streaming loop handles two chunks per trip and finishes with one or two
+    more.  With one workgroup per compute unit and these sizes the waves make
+    between one and six visits, odd and even, so every exit of the loop is
+    compared element by element (the large configurations only sample y and dx)."""
+    monkeypatch.setenv("GRKAN_FWD_WG_PER_CU", "1")
+    monkeypatch.setenv("GRKAN_BWD_WG_PER_CU", "1")
+    vec = 4 if dtype == "f32" else 8
+    per_pass = 256 * 4 * 64 * vec  # elements one pass of a 256-workgroup grid covers
+    for k, visits in enumerate((1.0, 1.5, 2.0, 2.6, 3.0, 3.7, 4.2, 5.0, 5.5)):
+        rows = int(visits * per_pass / D) + k
+        case = custom_case(9000 + k, rows, D, G, dtype)
+        gpu = run_gpu(case)
+        ref = run_oracle(oracle, case, threads=8)
+        assert_parity(gpu, ref, dtype, label="%dx%d G=%d %s (%.1f visits)" % (rows, D, G, dtype, visits))
+
+
 @pytest.mark.parametrize("dtype,offset", [("f32", 1), ("f32", 2), ("bf16", 1), ("bf16", 2), ("bf16", 4),
                                           ("f16", 1), ("f16", 2), ("f16", 4)])
 def test_misaligned_tensors_take_a_narrower_path(oracle, dtype, offset):
