@@ -103,3 +103,29 @@ def test_binding_refuses_cpu_tensors():
         grkan.grkan_fwd(x, A, B)
     with pytest.raises(ValueError):
         grkan.grkan_bwd(x, x, A, B)
+
+
+def test_headers_are_plain_c(tmp_path):
+    """The boundary is a C ABI: both headers must compile as C99 on their own,
+    in either order, with a call site for every entry point."""
+    import shutil
+    import subprocess
+
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_abi.c"
+    src.write_text(
+        '#include "grkan_alg1.h"\n#include "grkan.h"\n'
+        "int use(void *p, float *f, void *s) {\n"
+        "  grkan_plan_t pl; int32_t q[4];\n"
+        "  grkan_status_t st = grkan_plan(1, 8, 1, GRKAN_F16, 16, 256, 2, 0, &pl);\n"
+        "  st = grkan_fwd(p, f, f, p, 1, 8, 1, 5, 4, GRKAN_F32, s);\n"
+        "  st = grkan_bwd(p, p, f, f, p, f, f, p, grkan_bwd_workspace_bytes(1, 8, 1, GRKAN_BF16), 1, 8, 1, 5, 4, GRKAN_BF16, s);\n"
+        "  st = grkan_alg1_bwd(p, p, f, f, p, f, f, 1, 8, 1, s);\n"
+        "  st = grkan_device_query(q);\n"
+        "  return (int)st + (int)grkan_plan_cover_errors(1, 8, 1, GRKAN_F32, &pl) + (grkan_status_string(st) != 0);\n"
+        "}\n")
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                          "-I", str(ROOT / "include"), str(src)], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
