@@ -71,6 +71,9 @@ def parse_args():
     ap.add_argument("--mlp-block", action="store_true",
                     help="also time the KAT MLP block (two GR-KAN layers, torch GEMMs) against a standard "
                          "GELU MLP block, forward+backward, at the workload's x1 shape")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the HIP-graph leg (one rotation of steps captured once and replayed: what a "
+                         "launch-bound caller gains; the entry points only enqueue kernels)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of x2's size (for scaling profiler byte counters)")
     return ap.parse_args()
@@ -296,6 +299,37 @@ def main():
             dom.y[i % dom.sets].copy_(dom.x[i % dom.sets])
         torch.cuda.synchronize()
 
+    graph_replay = None
+    if not args.no_graph:
+        # one rotation over the buffer sets (so that a replay touches every set once; at most 64 steps),
+        # captured once.  Reported beside the eager figure, never instead of it.
+        try:
+            per_replay = min(64, max(layer.sets for layer in layers))
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step(0)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for i in range(per_replay):
+                    step(i)
+            replays = max(1, args.steps // per_replay)
+            for _ in range(2):
+                graph.replay()
+            torch.cuda.synchronize()
+            tg = time.perf_counter()
+            for _ in range(replays):
+                graph.replay()
+            torch.cuda.synchronize()
+            tg = (time.perf_counter() - tg) / (replays * per_replay)
+            graph_replay = {"steps_per_replay": per_replay, "replays": replays, "us_per_step": tg * 1e6,
+                            "elements_per_s": elems_per_step / tg, "eager_us_per_step": ms_per_step * 1e3}
+            del graph
+        except Exception as exc:  # the eager measurement above stands on its own
+            graph_replay = {"error": "%s: %s" % (type(exc).__name__, exc)}
+
     detail = None
     if not args.no_detail:
         # per kernel: 5 warm-ups, then 100 timed launches between HIP events (the paper's protocol),
@@ -409,6 +443,8 @@ def main():
         "roofline": roofline,
         "device": device_report(torch, grkan),
     }
+    if graph_replay is not None:
+        out["graph_replay"] = graph_replay
     if detail is not None:
         out["detail"] = detail
     if paper_micro is not None:
