@@ -404,3 +404,27 @@ def test_scales_bound_a_float32_evaluation(oracle):
     # and the plain relative error is unbounded by such a constant on these inputs either way
     plain = np.abs(evaluate(wide=True)[1] - dx) / np.abs(dx)
     assert plain.max() > 16 * eps
+
+
+# ---------------------------------------------------------------- change detector
+def test_oracle_results_have_not_moved(oracle):
+    """tests/golden/oracle_tiny_digest.txt was written by the committed script beside it, from the
+    oracle alone, when the pins above held.  Not a pin: it flags later edits that move the results."""
+    import importlib.util
+
+    spec = importlib.util.spec_from_file_location("write_oracle_digest", GOLDEN / "write_oracle_digest.py")
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = {}
+    for line in (GOLDEN / "oracle_tiny_digest.txt").read_text().splitlines():
+        if line.startswith("#") or not line.strip():
+            continue
+        m, n, key, *vals = line.split()
+        stored[(int(m), int(n), key)] = np.array([float(v) for v in vals])
+    for m, n in ((5, 4), (3, 2), (7, 6)):
+        d = mod.digest(m, n)
+        for key in ("sum_y", "wsum_y", "sum_dx", "wsum_dx", "dA", "dB"):
+            got = np.atleast_1d(np.array(d[key], dtype=np.float64))
+            want = stored[(m, n, key)]
+            scale = np.maximum(np.abs(want), 1e-3 * np.max(np.abs(want)))
+            assert np.all(np.abs(got - want) <= 1e-11 * scale), (m, n, key)
