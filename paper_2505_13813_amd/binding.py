@@ -43,6 +43,7 @@ class Plan(ctypes.Structure):
         ("chunk_stride", ctypes.c_int64),
         ("partials_per_group", ctypes.c_int32),
         ("lane_coef", ctypes.c_int32),
+        ("column_split", ctypes.c_int32),
     ]
 
     def as_dict(self):

@@ -415,9 +415,11 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
-    // group walk: the wave's group (scalar registers); flat walk: the group of
-    // this lane's fixed column (vector registers)
-    const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc) : id.g;
+    // group walk: the coefficient group that holds the wave's column block (scalar registers; the
+    // block is the group itself unless the plan splits groups); flat walk: the group of this lane's
+    // fixed column (vector registers)
+    const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc)
+                            : (int)((uint32_t)id.g * (uint32_t)p.dg / (uint32_t)a.dgc);
     const Coef<M, N> c = load_coef<M, N>(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
@@ -502,7 +504,8 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
-    const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc) : id.g;
+    const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc)
+                            : (int)((uint32_t)id.g * (uint32_t)p.dg / (uint32_t)a.dgc);
     const Coef<M, N> c = load_coef<M, N>(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
@@ -930,7 +933,7 @@ static grkan_status_t plan_resident(int64_t rows, int32_t D, int32_t G, grkan_dt
     if (st != GRKAN_OK)
         return st;
     // a single group is walked exactly like the flat walk (whole rows, contiguous per workgroup)
-    const bool rows_walk = pl->lane_coef || G == 1;
+    const bool rows_walk = pl->lane_coef || G * pl->column_split == 1;
     if (rows_walk && want.flat_walk != per_cu) {
         grkan_plan_t alt;
         if (make_plan(rows, D, G, io, align, info.num_cu, want.flat_walk, forward, &alt, nullptr) == GRKAN_OK &&

@@ -26,8 +26,10 @@ def test_walk_covers_every_vector_exactly_once(rows, D, G, io):
     for align, (num_cu, wg_per_cu), forward in itertools.product((16, 8, es), ((256, 4), (256, 8), (3, 1)),
                                                                 (False, True)):
         p = grkan.plan(rows, D, G, io, align_bytes=align, num_cu=num_cu, wg_per_cu=wg_per_cu, forward=forward)
-        walk_groups = 1 if p.lane_coef else G
+        walk_groups = 1 if p.lane_coef else G * p.column_split
         assert p.grid == (walk_groups // p.groups_per_wg) * p.wg_per_bundle
+        assert p.column_split == 1 or (not forward and not p.lane_coef and G < 4)
+        assert p.partials_per_group == (p.grid if p.lane_coef else p.wg_per_bundle * p.column_split)
         assert not p.lane_coef or p.fixed_col
         assert p.vec * es <= align and (D // G) % p.vec == 0
         assert grkan.plan_cover_errors(rows, D, G, io, p) == 0, p.as_dict()
@@ -50,6 +52,27 @@ def test_group_walk_bundles_groups_when_the_flat_walk_cannot_fix_columns():
     p = grkan.plan(rows, G * dg, G, GRKAN_F32)
     assert (p.fixed_col, p.lane_coef, p.groups_per_wg, p.waves_per_group_in_wg) == (0, 0, 4, 1)
     assert grkan.plan_cover_errors(rows, G * dg, G, GRKAN_F32, p) == 0
+
+
+def test_few_long_groups_are_walked_as_column_blocks():
+    # one group of 3072 float32 channels: four blocks of 768 (3072 bytes each); two groups: two blocks each
+    p = grkan.plan(50432, 3072, 1, GRKAN_F32)
+    assert (p.column_split, p.vecs_per_segment, p.lane_coef, p.fixed_col) == (4, 192, 0, 1)
+    assert p.grid == 4 * p.wg_per_bundle and p.partials_per_group == 4 * p.wg_per_bundle
+    p = grkan.plan(50432, 3072, 2, GRKAN_F32)
+    assert p.column_split == 2
+    # the blocks must stay whole cache lines, at least three: 192 float32 channels = 768 bytes split once only
+    p = grkan.plan(1000, 192, 1, GRKAN_F32)
+    assert (p.column_split, p.vecs_per_segment) == (2, 24)
+    # ... and whole vectors: 96 channels of bfloat16 = 192 bytes cannot be split
+    assert grkan.plan(1000, 96, 1, GRKAN_BF16).column_split == 1
+    # the forward pass and four or more groups are left alone
+    assert grkan.plan(50432, 3072, 1, GRKAN_F32, forward=True).column_split == 1
+    assert grkan.plan(50432, 3072, 4, GRKAN_F32).column_split == 1
+    for rows, D, G in ((130, 3072, 1), (77, 1536, 2), (64, 768, 3), (5, 7, 1)):
+        for io in (GRKAN_F32, GRKAN_BF16):
+            p = grkan.plan(rows, D, G, io)
+            assert grkan.plan_cover_errors(rows, D, G, io, p) == 0, (rows, D, G, io, p.as_dict())
 
 
 def test_headline_plans():
