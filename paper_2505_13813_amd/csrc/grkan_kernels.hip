@@ -385,7 +385,7 @@ struct FwdArgs {
     char *y;
     const float *A;
     const float *B;
-    int32_t dgc; // channels per coefficient group (differs from walk.dg in the flat walk)
+    int32_t dgc; // channels per coefficient group (walk.dg is the walk's: a whole row in the flat walk)
     Walk walk;
 };
 
@@ -397,7 +397,8 @@ struct BwdArgs {
     const float *B;
     float *partial; // [G][rows_per_group][m + 1 + n]
     int32_t Gc;     // coefficient groups
-    int32_t dgc;    // channels per coefficient group (differs from walk.dg in the flat walk)
+    int32_t dgc;    // channels per coefficient group (walk.dg is the walk's: a whole row in the flat walk,
+                    // a column block of the group when the plan splits groups)
     Walk walk;
 };
 
