@@ -166,6 +166,22 @@ def test_large_inputs_stay_finite(oracle):
     assert_parity(gpu, ref, "f32", label="large |x|")
 
 
+def test_float16_results_beyond_the_format_become_infinities(oracle):
+    # B = 0 makes F a polynomial: with |x| up to 40 some |y| pass 65504, the largest binary16 number
+    case = custom_case(13, 64, 96, 4, "f16", x_scale=10.0)
+    case["B"] = np.zeros_like(case["B"])
+    gpu = run_gpu(case)
+    ref = run_oracle(oracle, case)
+    over = np.abs(ref["y"]) > 65520.0          # rounds to infinity (half-way point above 65504)
+    safe = np.abs(ref["y"]) < 65504.0
+    assert over.any() and safe.any()
+    assert np.all(np.isinf(gpu["y"][over])) and np.all(np.sign(gpu["y"][over]) == np.sign(ref["y"][over]))
+    err = np.abs(gpu["y"][safe] - ref["y"][safe]) / np.maximum(np.abs(ref["y"][safe]), ref["Sy"][safe])
+    assert np.max(np.maximum(err - 2.0 ** -25 / np.maximum(np.abs(ref["y"][safe]), 1e-30), 0.0)) <= TOL["f16"]["y"]
+    # the coefficient sums are float32 and stay finite
+    assert np.all(np.isfinite(gpu["dA"])) and np.all(gpu["dB"] == 0.0)
+
+
 def test_empty_input():
     import torch
 
