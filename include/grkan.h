@@ -79,19 +79,20 @@ const char *grkan_status_string(grkan_status_t status);
  */
 typedef struct {
     int32_t vec;                  /* elements per lane per memory access */
-    int32_t vecs_per_segment;     /* d_g / column_split / vec (D / vec in the flat walk) */
+    int32_t vecs_per_segment;     /* d_g / column_split / vec (D / column_split / vec in the flat walk) */
     int32_t waves_per_wg;         /* wavefronts in a workgroup */
     int32_t groups_per_wg;        /* adjacent groups that share a workgroup */
     int32_t waves_per_group_in_wg;/* waves_per_wg / groups_per_wg */
     int32_t wg_per_bundle;        /* workgroups that share one bundle of groups */
     int32_t grid;                 /* workgroups launched = (walk groups / groups_per_wg) * wg_per_bundle,
-                                     walk groups = G * column_split (1 in the flat walk) */
+                                     walk groups = G * column_split (column_split in the flat walk) */
     int32_t fixed_col;            /* 1: every lane keeps its column for the whole kernel */
     int64_t chunk_stride;         /* 64-vector chunks between two visits of one wavefront */
     int32_t partials_per_group;   /* rows of m+1+n floats each group contributes to the workspace */
     int32_t lane_coef;            /* 1: flat walk with per-lane coefficients (then fixed_col = 1) */
-    int32_t column_split;         /* group walk: column blocks per group, each walked like a group of its own
-                                     (backward pass with fewer than four groups; 1 otherwise) */
+    int32_t column_split;         /* backward pass only (1 otherwise).  Group walk: column blocks per group, each
+                                     walked like a group of its own (fewer than four groups).  Flat walk:
+                                     column blocks per row, each of whole groups and walked on its own */
 } grkan_plan_t;
 
 /*

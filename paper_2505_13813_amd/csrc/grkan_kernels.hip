@@ -395,8 +395,7 @@ struct BwdArgs {
     char *dx;
     const float *A;
     const float *B;
-    float *partial; // [G][rows_per_group][m + 1 + n]
-    int32_t Gc;     // coefficient groups
+    float *partial; // [G][workspace rows per group][m + 1 + n]
     int32_t dgc;    // channels per coefficient group (walk.dg is the walk's: a whole row in the flat walk,
                     // a column block of the group when the plan splits groups)
     Walk walk;
@@ -418,9 +417,10 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
     const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
     // group walk: the coefficient group that holds the wave's column block (scalar registers; the
     // block is the group itself unless the plan splits groups); flat walk: the group of this lane's
-    // fixed column (vector registers)
-    const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc)
-                            : (int)((uint32_t)id.g * (uint32_t)p.dg / (uint32_t)a.dgc);
+    // fixed column inside the wave's block of whole groups (vector registers)
+    const int cg = (int)(((uint32_t)id.g * (uint32_t)p.dg +
+                          (LANECOEF ? fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec : 0u)) /
+                         (uint32_t)a.dgc);
     const Coef<M, N> c = load_coef<M, N>(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
@@ -505,8 +505,9 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
-    const int cg = LANECOEF ? (int)(fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec / (uint32_t)a.dgc)
-                            : (int)((uint32_t)id.g * (uint32_t)p.dg / (uint32_t)a.dgc);
+    const int cg = (int)(((uint32_t)id.g * (uint32_t)p.dg +
+                          (LANECOEF ? fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec : 0u)) /
+                         (uint32_t)a.dgc);
     const Coef<M, N> c = load_coef<M, N>(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
@@ -624,11 +625,12 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
         }
     } else {
         // Flat walk: the 256 lanes of the workgroup hold consecutive vectors of
-        // the rows, so lanes of one coefficient group form runs of vt = d_g / vec
-        // lanes (a group can own several runs when a row is shorter than the
-        // workgroup).  registers -> LDS -> one sum per run (fixed lane order) ->
-        // one sum per group (fixed run order) -> one workspace row per group and
-        // workgroup, zeros included, so that stage 2 needs no map of who wrote what.
+        // the rows of its column block, so lanes of one coefficient group form
+        // runs of vt = d_g / vec lanes (a group can own several runs when the
+        // block's row is shorter than the workgroup).  registers -> LDS -> one sum
+        // per run (fixed lane order) -> one sum per group (fixed run order) -> one
+        // workspace row per workgroup for every group of the block, zeros
+        // included, so that stage 2 needs no map of who wrote what.
         __shared__ float lane_part[kNumCoef][kThreadsPerWg];
         __shared__ float run_part[kThreadsPerWg + 1][kNumCoef];
         const int tid = threadIdx.x;
@@ -637,8 +639,9 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
             lane_part[k][tid] = acc[k];
         __syncthreads();
         const uint32_t vt = (uint32_t)a.dgc / (uint32_t)p.vec; // lanes per run
-        const uint32_t V = (uint32_t)p.v;                       // vectors per row
-        const uint32_t c0 = ((uint32_t)blockIdx.x * kThreadsPerWg) % V; // column of lane 0
+        const uint32_t V = (uint32_t)p.v;                       // vectors per row of the walk's column block
+        const uint32_t Gb = (uint32_t)p.dg / (uint32_t)a.dgc;   // coefficient groups per column block
+        const uint32_t c0 = ((uint32_t)id.wg_index * kThreadsPerWg) % V; // column of lane 0
         const uint32_t u0 = c0 / vt;                            // first (unwrapped) run
         const uint32_t n_runs = (c0 + kThreadsPerWg - 1) / vt - u0 + 1;
         for (uint32_t item = tid; item < n_runs * kNumCoef; item += kThreadsPerWg) {
@@ -652,14 +655,14 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
             run_part[r][k] = s;
         }
         __syncthreads();
-        const uint32_t G = (uint32_t)a.Gc;
-        for (uint32_t item = tid; item < G * kNumCoef; item += kThreadsPerWg) {
+        for (uint32_t item = tid; item < Gb * kNumCoef; item += kThreadsPerWg) {
             const uint32_t g = item / kNumCoef, k = item - g * kNumCoef;
-            // run r belongs to group (u0 + r) mod G
+            // run r belongs to group (u0 + r) mod Gb of this block
             float s = 0.0f;
-            for (uint32_t r = (g + G - u0 % G) % G; r < n_runs; r += G)
+            for (uint32_t r = (g + Gb - u0 % Gb) % Gb; r < n_runs; r += Gb)
                 s += run_part[r][k];
-            a.partial[((int64_t)g * gridDim.x + blockIdx.x) * kNumCoef + k] = s;
+            const int64_t gg = (int64_t)id.g * Gb + g; // the group's index in A, B and the workspace
+            a.partial[(gg * p.wg_per_bundle + id.wg_index) * kNumCoef + k] = s;
         }
     }
 }
@@ -897,9 +900,8 @@ static int resident_wg_per_cu(const void *kernel, int dev)
 // Workgroups (of 4 waves) per compute unit the persistent grids are sized for.
 // With one chunk of loads in flight per wave (1 KB forward, 2 KB backward),
 // 4 and 2 workgroups per unit put about 4 MB of loads in flight on 256 units,
-// which is where the HBM-bound kernels were measured fastest (the flat walk's
-// backward pass, with its coefficients in vector registers and a longer
-// epilogue, measured best at 3).  The bfloat16 backward pass moves half the
+// which is where the HBM-bound kernels were measured fastest (a backward pass
+// that sweeps whole rows as one stream - no column blocks - measured best at 3).  The bfloat16 backward pass moves half the
 // bytes for the same arithmetic and is bound by the vector ALU instead: it
 // takes every wave slot it can get (requests are clamped to the kernel's real
 // occupancy).  The environment variables override both walks for experiments.
@@ -933,8 +935,9 @@ static grkan_status_t plan_resident(int64_t rows, int32_t D, int32_t G, grkan_dt
     grkan_status_t st = make_plan(rows, D, G, io, align, info.num_cu, per_cu, forward, pl, walk);
     if (st != GRKAN_OK)
         return st;
-    // a single group is walked exactly like the flat walk (whole rows, contiguous per workgroup)
-    const bool rows_walk = pl->lane_coef || G * pl->column_split == 1;
+    // one sweep over whole rows (flat walk without column blocks, or a single unsplit group) against
+    // several interleaved column streams: the two were measured best at different grid sizes
+    const bool rows_walk = (pl->lane_coef ? pl->column_split : G * pl->column_split) == 1;
     if (rows_walk && want.flat_walk != per_cu) {
         grkan_plan_t alt;
         if (make_plan(rows, D, G, io, align, info.num_cu, want.flat_walk, forward, &alt, nullptr) == GRKAN_OK &&
@@ -1103,7 +1106,6 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
     a.A = A;
     a.B = B;
     a.partial = static_cast<float *>(workspace);
-    a.Gc = G;
     a.dgc = D / G;
     if (pl.grid > 0) {
         void *args[] = {&a};

@@ -142,13 +142,26 @@ grkan_status_t make_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t io, i
     const int64_t seg_bytes = (int64_t)dg * es;
     const bool short_segments = G > 1 && (forward || seg_bytes < 3 * kLineBytes || seg_bytes % kLineBytes != 0);
     if (short_segments && rows > 0) {
-        st = plan_walk(rows, D, 1, vec, es, num_cu, wg_per_cu, out);
-        if (st == GRKAN_OK && out->fixed_col) {
-            out->lane_coef = 1;
-            out->partials_per_group = out->grid; // every workgroup writes one row per group
-            if (walk)
-                return walk_from_plan(rows, D, G, io, *out, walk);
-            return GRKAN_OK;
+        // The backward pass prefers the flat walk over a few column blocks of whole groups to one
+        // sweep over whole rows, for the reason given at pick_column_split; the forward pass, one
+        // read and one write per element, was measured no faster that way.
+        const int32_t blocks_to_try[] = {8, 4, 2, 1};
+        for (int32_t blocks : blocks_to_try) {
+            if (blocks > 1) {
+                const int64_t block_bytes = (int64_t)(D / blocks) * es;
+                if (forward || G % blocks != 0 || block_bytes % kLineBytes != 0 || block_bytes < 3 * kLineBytes)
+                    continue;
+            }
+            st = plan_walk(rows, D, blocks, vec, es, num_cu, wg_per_cu, out);
+            if (st == GRKAN_OK && out->fixed_col && out->groups_per_wg == 1) {
+                out->lane_coef = 1;
+                out->column_split = blocks;
+                // every workgroup of a block writes one row for each group of that block
+                out->partials_per_group = out->wg_per_bundle;
+                if (walk)
+                    return walk_from_plan(rows, D, G, io, *out, walk);
+                return GRKAN_OK;
+            }
         }
     }
     const int32_t split = forward ? 1 : pick_column_split(G, dg, vec, es);
@@ -170,9 +183,10 @@ grkan_status_t walk_from_plan(int64_t rows, int32_t D, int32_t G, grkan_dtype_t 
         return st;
     if (pl.vec <= 0 || (D / G) % pl.vec != 0)
         return GRKAN_ERR_SHAPE;
-    if (pl.column_split < 1 || (pl.lane_coef && pl.column_split != 1) || (D / G) % pl.column_split != 0)
+    if (pl.column_split < 1 || (pl.lane_coef ? G % pl.column_split != 0 : (D / G) % pl.column_split != 0))
         return GRKAN_ERR_SHAPE;
-    const int32_t Gw = pl.lane_coef ? 1 : G * pl.column_split; // groups of the walk
+    // groups of the walk: column blocks of whole coefficient groups (flat walk) or of one group each
+    const int32_t Gw = pl.lane_coef ? pl.column_split : G * pl.column_split;
     const int32_t dg = D / Gw;
     if (pl.vecs_per_segment != dg / pl.vec || pl.groups_per_wg <= 0 ||
         Gw % pl.groups_per_wg != 0 || pl.waves_per_wg != kWavesPerWg || pl.waves_per_wg % pl.groups_per_wg != 0 ||

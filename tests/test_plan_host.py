@@ -26,10 +26,11 @@ def test_walk_covers_every_vector_exactly_once(rows, D, G, io):
     for align, (num_cu, wg_per_cu), forward in itertools.product((16, 8, es), ((256, 4), (256, 8), (3, 1)),
                                                                 (False, True)):
         p = grkan.plan(rows, D, G, io, align_bytes=align, num_cu=num_cu, wg_per_cu=wg_per_cu, forward=forward)
-        walk_groups = 1 if p.lane_coef else G * p.column_split
+        walk_groups = p.column_split if p.lane_coef else G * p.column_split
         assert p.grid == (walk_groups // p.groups_per_wg) * p.wg_per_bundle
-        assert p.column_split == 1 or (not forward and not p.lane_coef and G < 4)
-        assert p.partials_per_group == (p.grid if p.lane_coef else p.wg_per_bundle * p.column_split)
+        assert p.column_split == 1 or (not forward and (p.lane_coef or G < 4))
+        assert not p.lane_coef or G % p.column_split == 0
+        assert p.partials_per_group == p.wg_per_bundle * (1 if p.lane_coef else p.column_split)
         assert not p.lane_coef or p.fixed_col
         assert p.vec * es <= align and (D // G) % p.vec == 0
         assert grkan.plan_cover_errors(rows, D, G, io, p) == 0, p.as_dict()
@@ -83,13 +84,14 @@ def test_headline_plans():
     assert (p.vec, p.groups_per_wg, p.waves_per_group_in_wg, p.fixed_col) == (4, 1, 4, 1)
     assert p.grid <= 256 * 4 and p.grid >= 256 * 4 * 0.95
     assert (64 * p.chunk_stride) % p.vecs_per_segment == 0
-    # KAT-B x1 bf16: 192-byte segments -> flat walk over whole rows, coefficients per lane
+    # KAT-B x1 bf16: 192-byte segments -> flat walk, coefficients per lane; the 1536-byte rows are walked
+    # as four column blocks of two groups (384 bytes) each
     p = grkan.plan(25216, 768, 8, GRKAN_BF16)
-    assert (p.vec, p.lane_coef, p.fixed_col, p.vecs_per_segment) == (8, 1, 1, 96)
-    assert p.partials_per_group == p.grid
-    # stress with 64 groups of 48 channels: flat walk as well
+    assert (p.vec, p.lane_coef, p.fixed_col, p.column_split, p.vecs_per_segment) == (8, 1, 1, 4, 24)
+    assert p.partials_per_group == p.wg_per_bundle and p.grid == 4 * p.wg_per_bundle
+    # stress with 64 groups of 48 channels: flat walk as well, eight blocks of eight groups
     p = grkan.plan(50432, 3072, 64, GRKAN_F32)
-    assert p.lane_coef == 1
+    assert (p.lane_coef, p.column_split, p.vecs_per_segment) == (1, 8, 96)
     # stress, one group
     p = grkan.plan(50432, 3072, 1, GRKAN_F32)
     assert p.groups_per_wg == 1 and p.fixed_col == 1
