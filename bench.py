@@ -36,8 +36,8 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: 256 CUs x 
 # SQ_INSTS_VALU counter at the KAT-B x2 shape (wave instructions x 64 lanes / elements; the summary is under
 # profiles/).  Every instruction is priced as one issue slot, the reciprocal included.
 BWD_VALU_INSTR_16BIT = {
-    ("bf16", 3, 2): 30.46, ("bf16", 5, 4): 44.90, ("bf16", 7, 6): 58.67,
-    ("f16", 3, 2): 30.52, ("f16", 5, 4): 44.77, ("f16", 7, 6): 58.93,
+    ("bf16", 3, 2): 30.52, ("bf16", 5, 4): 44.97, ("bf16", 7, 6): 58.71,
+    ("f16", 3, 2): 30.58, ("f16", 5, 4): 44.83, ("f16", 7, 6): 58.98,
 }
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs

@@ -418,9 +418,12 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_fwd_kernel(const FwdArgs 
     // group walk: the coefficient group that holds the wave's column block (scalar registers; the
     // block is the group itself unless the plan splits groups); flat walk: the group of this lane's
     // fixed column inside the wave's block of whole groups (vector registers)
-    const int cg = (int)(((uint32_t)id.g * (uint32_t)p.dg +
-                          (LANECOEF ? fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec : 0u)) /
-                         (uint32_t)a.dgc);
+    int cg;
+    if constexpr (LANECOEF)
+        cg = (int)(((uint32_t)id.g * (uint32_t)p.dg + fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec) /
+                   (uint32_t)a.dgc);
+    else
+        cg = p.dg == a.dgc ? id.g : (int)((uint32_t)id.g * (uint32_t)p.dg / (uint32_t)a.dgc);
     const Coef<M, N> c = load_coef<M, N>(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
@@ -505,9 +508,12 @@ __global__ __launch_bounds__(kThreadsPerWg) void grkan_bwd_stage1_kernel(const B
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const WaveId id = wave_id(p, (int32_t)blockIdx.x, wv);
-    const int cg = (int)(((uint32_t)id.g * (uint32_t)p.dg +
-                          (LANECOEF ? fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec : 0u)) /
-                         (uint32_t)a.dgc);
+    int cg;
+    if constexpr (LANECOEF)
+        cg = (int)(((uint32_t)id.g * (uint32_t)p.dg + fixed_lane_col(p, id.w, lane).ccol * (uint32_t)p.vec) /
+                   (uint32_t)a.dgc);
+    else
+        cg = p.dg == a.dgc ? id.g : (int)((uint32_t)id.g * (uint32_t)p.dg / (uint32_t)a.dgc);
     const Coef<M, N> c = load_coef<M, N>(a.A, a.B, cg);
     const int32_t n_it = full_visits(p, id.w);
     const bool tail = owns_tail(p, id.w) && lane < p.rem;
