@@ -73,9 +73,12 @@ const char *grkan_status_string(grkan_status_t status);
  * workgroup holds `groups_per_wg` adjacent groups.  Flat walk (lane_coef = 1),
  * chosen by the forward pass always and by the backward pass when a group's
  * row segment is shorter than 384 bytes or not a whole number of 128-byte
- * lines: wavefronts walk whole rows (the plan is that of a
- * single group of D channels) and every lane keeps the coefficients of the
- * group its fixed column belongs to.
+ * lines: wavefronts walk whole rows, or in the backward pass column blocks of
+ * whole groups (the plan is that of `column_split` groups of D / column_split
+ * channels), and every lane keeps the coefficients of the group its fixed
+ * column belongs to.  In the backward pass a group walk over fewer than four
+ * groups cuts each group into `column_split` column blocks that are walked
+ * like groups of their own.
  */
 typedef struct {
     int32_t vec;                  /* elements per lane per memory access */
