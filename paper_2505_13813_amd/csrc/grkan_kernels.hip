@@ -13,9 +13,9 @@
 //            one group, coefficients in scalar registers; the wavefront folds
 //            its sums with DPP row/bank operations, the workgroup folds its
 //            wavefronts through LDS.  Flat walk (short segments): wavefronts
-//            read whole rows, each lane holds the coefficients of its fixed
-//            column's group, and the workgroup folds lanes -> runs -> groups
-//            through LDS.  Either way one row of m + 1 + n floats per (workgroup,
+//            read whole rows or column blocks of whole groups, each lane holds
+//            the coefficients of its fixed column's group, and the workgroup
+//            folds lanes -> runs -> groups through LDS.  Either way one row of m + 1 + n floats per (workgroup,
 //            group) goes to a workspace.
 //   stage 2  one wavefront per group adds that group's workspace rows in a
 //            fixed order (in double) and overwrites dA / dB.

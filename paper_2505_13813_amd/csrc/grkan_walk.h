@@ -13,10 +13,12 @@
 // arranges whenever it can) a lane keeps its column and its row offset inside
 // the chunk for the whole kernel and only a wave-uniform base advances.
 //
-// The same walk with a single group of D channels is the "flat" walk over
-// whole rows: wavefronts then read contiguous kilobytes whatever d_g is, and
-// because columns are fixed each lane belongs to one coefficient group for the
-// whole kernel and keeps that group's coefficients in vector registers.
+// The same walk with a single group of D channels (or a few column blocks of
+// whole coefficient groups) is the "flat" walk: wavefronts then read
+// contiguous kilobytes whatever d_g is, and because columns are fixed each
+// lane belongs to one coefficient group for the whole kernel and keeps that
+// group's coefficients in vector registers.  Likewise a walk group can be a
+// column block of one coefficient group (few, long groups are cut up).
 #ifndef GRKAN_WALK_H_
 #define GRKAN_WALK_H_
 
