@@ -129,3 +129,8 @@ def test_headers_are_plain_c(tmp_path):
     res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
                           "-I", str(ROOT / "include"), str(src)], capture_output=True, text=True)
     assert res.returncode == 0, res.stderr
+
+
+def test_device_query_rejects_a_null_pointer():
+    lib = grkan.load_library()
+    assert lib.grkan_device_query(None) == 1

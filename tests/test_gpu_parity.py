@@ -182,6 +182,14 @@ def test_float16_results_beyond_the_format_become_infinities(oracle):
     assert np.all(np.isfinite(gpu["dA"])) and np.all(gpu["dB"] == 0.0)
 
 
+def test_device_query_reports_the_chip():
+    import paper_2505_13813_amd as grkan
+
+    q = grkan.device_query()
+    assert q["compute_units"] >= 64 and q["engine_clock_khz"] > 500_000
+    assert q["memory_clock_khz"] > 100_000 and q["memory_bus_bits"] >= 1024
+
+
 def test_empty_input():
     import torch
 
