@@ -213,20 +213,26 @@ int grkan_oracle_bwd(const double *x, const double *dy, const double *A, const d
 
 /*
  * Condition scales for the error metric used by the parity tests (not part of
- * the method): the paper's expressions with every monomial replaced by its
- * magnitude, i.e. the size the result would have if nothing cancelled inside
- * P, P' and Aden'.  Q itself is taken as exact (the GPU kernels evaluate Aden
- * in double for float32 I/O precisely so that it is).
+ * the method).
+ *
+ * Elementwise results: the paper's expressions with every monomial of P, P'
+ * and Aden' replaced by its magnitude, i.e. the size the result would have if
+ * nothing cancelled inside those polynomials.  Q itself is taken as exact (the
+ * GPU kernels evaluate Aden in double for float32 I/O precisely so that it is).
  *
  *   Sy  = Pm / Q
  *   Sdx = |dy| ( dPm / Q + dAm Pm / Q^2 )
- *   RA[g][i]   = sqrt( sum (dy x^i / Q)^2 )
- *   RB[g][j-1] = sqrt( sum (dy x^j s Pm / Q^2)^2 )
  *
  * with Pm = sum |a_i||x|^i, dPm = sum i|a_i||x|^(i-1), dAm = sum j|b_j||x|^(j-1).
- * Where nothing cancels, Sy = |y|, Sdx >= |dx| within a factor 2, and RA, RB
- * are the root-sum-squares of the summed terms (the scale of the rounding
- * error of any summation order).
+ * Where nothing cancels, Sy = |y| and Sdx >= |dx| within a factor 2.
+ *
+ * Coefficient gradients: the root-sum-square of the very terms that
+ * Eq. "accum" and "accum2" add up, with the actual P (no magnitude
+ * replacement), which is the scale of the rounding error of any summation
+ * order:
+ *
+ *   RA[g][i]   = sqrt( sum (dy x^i / Q)^2 )
+ *   RB[g][j-1] = sqrt( sum (dy x^j s P / Q^2)^2 )
  *
  * Any of the output pointers may be NULL.  dy may be NULL when only Sy is wanted.
  * The root-sum-squares are plain (uncompensated) double sums: they only scale a tolerance.
@@ -282,7 +288,7 @@ int grkan_oracle_scales(const double *x, const double *dy, const double *A, cons
                 sq[(size_t)g * nc + i] += t * t;
             }
             for (int j = 1; j <= n; ++j) {
-                double t = d * axp[j] * fabs(e.s) * Pm / Q2;
+                double t = d * axp[j] * fabs(e.s) * fabs(e.P) / Q2;
                 sq[(size_t)g * nc + m + j] += t * t;
             }
         }
