@@ -40,13 +40,28 @@ BWD_VALU_INSTR_16BIT = {
     ("f16", 3, 2): 30.58, ("f16", 5, 4): 44.83, ("f16", 7, 6): 58.98,
 }
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); the
-# summaries are under profiles/.  None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/bench_kat_b_f32_hbm_traffic.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB, stage 1 + stage 2
-    "kat_b/f32/bwd_x2": 908021 * 1024,
-}
+WORKLOAD_LABEL = {"tiny": "tiny [4,197,192]", "kat_t": "KAT-T", "kat_s": "KAT-S", "kat_b": "KAT-B",
+                  "stress": "stress [256,197,3072]"}
+
+
+def measured_traffic(key):
+    """HBM bytes per launch of the dominant kernel as rocprofv3 --pmc counted them
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size) in an earlier,
+    separate profiler run: read from the tracked summaries under profiles/, which
+    carry one line `traffic_bytes_per_launch[<workload>/<dtype>/<kernel>] = <bytes>`
+    per measured kernel.  Returns (bytes, file name) or (None, None): nothing is
+    counted in this run itself."""
+    import re
+
+    pat = re.compile(r"^traffic_bytes_per_launch\[%s\]\s*=\s*(\d+)\s*$" % re.escape(key), re.M)
+    for f in sorted((ROOT / "profiles").glob("*.txt")):
+        m = pat.search(f.read_text())
+        if m:
+            return int(m.group(1)), "profiles/" + f.name
+    return None, None
+
+
+IO_CODE = {"f32": 0, "bf16": 1, "f16": 2}  # grkan_dtype_t
 
 
 def parse_args():
@@ -99,7 +114,7 @@ class Layer:
         self.dx = [torch.empty_like(first["x"]) for _ in range(sets)]
         self.dA = torch.empty_like(self.A)
         self.dB = torch.empty_like(self.B)
-        io = grkan.GRKAN_F32 if case["dtype"] == "f32" else grkan.GRKAN_BF16
+        io = IO_CODE[case["dtype"]]
         need = grkan.grkan_bwd_workspace_bytes(self.rows, self.D, self.G, io)
         self.ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
         self.grkan = grkan
@@ -275,9 +290,10 @@ def main():
     what = "grkan_bwd on %s [%d,%d] (stage 1 + stage 2)" % (dom_name, dom.rows, dom.D)
     if args.dtype == "f32" or slots is None:
         achieved = dom.bwd_bytes() / (dom_ms * 1e-3) / 1e9
+        traffic, traffic_src = measured_traffic(key)
         roofline = {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(key),
+            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
             "kernel": "%s, %d algorithmic bytes per launch, avg %.2f us" % (what, dom.bwd_bytes(), dom_ms * 1e3),
         }
     else:
@@ -425,8 +441,8 @@ def main():
             block[dt_name] = res
 
     out = {
-        "metric": "GR-KAN fwd+bwd elements/s and achieved HBM GB/s (% of peak), KAT-"
-                  + args.workload[-1].upper() + " shape",
+        "metric": "GR-KAN fwd+bwd elements/s and achieved HBM GB/s (% of peak), %s shape"
+                  % WORKLOAD_LABEL[args.workload],
         "value": elems_per_step / (dt / args.steps),
         "unit": "elements/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

@@ -136,6 +136,16 @@ size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, grkan_dtype
 grkan_status_t grkan_device_query(int32_t *out);
 
 /*
+ * For experiments and tests (no operation of the paper): workgroups per compute
+ * unit the persistent grids of the forward and of the backward pass are sized
+ * for; 0 restores the built-in choice.  The environment variables
+ * GRKAN_FWD_WG_PER_CU and GRKAN_BWD_WG_PER_CU give the initial values and are
+ * read once, when the library is loaded.  Results do not depend on the setting
+ * beyond the summation order of dA / dB; grkan_bwd_workspace_bytes follows it.
+ */
+void grkan_tuning_override(int32_t fwd_wg_per_cu, int32_t bwd_wg_per_cu);
+
+/*
  * Forward (Eq. "pade"):  y[r, c] = P_g(x[r, c]) / (1 + |Aden_g(x[r, c])|).
  * y may alias x.
  */

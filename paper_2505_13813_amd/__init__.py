@@ -21,4 +21,5 @@ from .binding import (  # noqa: F401
     plan,
     plan_cover_errors,
     status_string,
+    tuning_override,
 )

@@ -22,6 +22,7 @@ N_DEGREE = 4
 DEGREES = ((5, 4), (3, 2), (7, 6))
 
 _lib = None
+_ws_bytes_cache = {}
 
 
 class GrkanError(RuntimeError):
@@ -76,6 +77,8 @@ def load_library():
     lib.grkan_plan_cover_errors.restype = i64
     lib.grkan_device_query.argtypes = [ctypes.POINTER(ctypes.c_int32)]
     lib.grkan_device_query.restype = ctypes.c_int
+    lib.grkan_tuning_override.argtypes = [i32, i32]
+    lib.grkan_tuning_override.restype = None
     lib.grkan_bwd_workspace_bytes.argtypes = [i64, i32, i32, ctypes.c_int]
     lib.grkan_bwd_workspace_bytes.restype = sz
     lib.grkan_fwd.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, ctypes.c_int, vp]
@@ -118,6 +121,13 @@ def device_query() -> dict:
     return {"compute_units": out[0], "engine_clock_khz": out[1], "memory_clock_khz": out[2], "memory_bus_bits": out[3]}
 
 
+def tuning_override(fwd_wg_per_cu: int = 0, bwd_wg_per_cu: int = 0) -> None:
+    """Experiments and tests: size the persistent grids for this many workgroups per
+    compute unit (0 = the built-in choice).  Cached workspace sizes are dropped."""
+    load_library().grkan_tuning_override(int(fwd_wg_per_cu), int(bwd_wg_per_cu))
+    _ws_bytes_cache.clear()
+
+
 def grkan_bwd_workspace_bytes(rows: int, D: int, G: int, io: int) -> int:
     return int(load_library().grkan_bwd_workspace_bytes(rows, D, G, io))
 
@@ -148,8 +158,8 @@ def _io_of(t) -> int:
 def _check(x, A, B) -> Tuple[int, int, int]:
     import torch
 
-    if not x.is_cuda or not A.is_cuda or not B.is_cuda:
-        raise ValueError("grkan runs on the GPU only: tensors must be on a HIP device")
+    if not x.is_cuda or A.device != x.device or B.device != x.device:
+        raise ValueError("grkan runs on the GPU only: tensors must be on one HIP device")
     if not x.is_contiguous() or not A.is_contiguous() or not B.is_contiguous():
         raise ValueError("tensors must be contiguous")
     if A.dtype != torch.float32 or B.dtype != torch.float32:
@@ -176,7 +186,7 @@ def grkan_fwd(x, A, B, out=None, stream=None):
 
     rows, D, G = _check(x, A, B)
     y = torch.empty_like(x) if out is None else out
-    if y.shape != x.shape or y.dtype != x.dtype or not y.is_contiguous() or not y.is_cuda:
+    if y.shape != x.shape or y.dtype != x.dtype or not y.is_contiguous() or y.device != x.device:
         raise ValueError("out must match x")
     st = grkan_fwd_raw(x.data_ptr(), A.data_ptr(), B.data_ptr(), y.data_ptr(), rows, D, G, _io_of(x),
                        _stream_ptr(stream), int(A.shape[1]) - 1, int(B.shape[1]))
@@ -185,13 +195,41 @@ def grkan_fwd(x, A, B, out=None, stream=None):
     return y
 
 
+def _workspace_bytes_cached(rows: int, D: int, G: int, io: int, device_index: int) -> int:
+    """grkan_bwd_workspace_bytes plans the launch for every built degree pair and
+    alignment; the answer depends on (shape, dtype, device) only, so it is kept."""
+    key = (rows, D, G, io, device_index)
+    need = _ws_bytes_cache.get(key)
+    if need is None:
+        need = grkan_bwd_workspace_bytes(rows, D, G, io)
+        if need == 0:
+            raise GrkanError(7, "grkan_bwd_workspace_bytes")
+        _ws_bytes_cache[key] = need
+    return need
+
+
+def _check_bwd_outputs(x, A, B, dx, dA, dB):
+    import torch
+
+    if dx.shape != x.shape or dx.dtype != x.dtype or not dx.is_contiguous() or dx.device != x.device:
+        raise ValueError("dx must match x in shape, dtype, device and be contiguous")
+    for name, t, like in (("dA", dA, A), ("dB", dB, B)):
+        if t.shape != like.shape or t.dtype != torch.float32 or not t.is_contiguous() or t.device != x.device:
+            raise ValueError("%s must be a contiguous float32 tensor of the shape of %s on the device of x"
+                             % (name, name[1:]))
+
+
 def grkan_bwd(x, dy, A, B, workspace: Optional["torch.Tensor"] = None, out=None, stream=None):
     """(dx, dA, dB) of the group-wise rational function (Eq. "grad_x", "grad_a",
-    "grad_b", "accum", "accum2").  dA, dB are float32 and overwritten."""
+    "grad_b", "accum", "accum2").  dA, dB are float32 and overwritten.
+
+    `workspace`: a contiguous uint8 tensor on the device of x of at least
+    grkan_bwd_workspace_bytes(...) bytes (the library checks the size); one is
+    allocated when none is passed."""
     import torch
 
     rows, D, G = _check(x, A, B)
-    if dy.shape != x.shape or dy.dtype != x.dtype or not dy.is_contiguous() or not dy.is_cuda:
+    if dy.shape != x.shape or dy.dtype != x.dtype or not dy.is_contiguous() or dy.device != x.device:
         raise ValueError("dy must match x")
     io = _io_of(x)
     if out is None:
@@ -200,15 +238,16 @@ def grkan_bwd(x, dy, A, B, workspace: Optional["torch.Tensor"] = None, out=None,
         dB = torch.empty_like(B)
     else:
         dx, dA, dB = out
-    need = grkan_bwd_workspace_bytes(rows, D, G, io)
-    if need == 0:
-        raise GrkanError(7, "grkan_bwd_workspace_bytes")
+        _check_bwd_outputs(x, A, B, dx, dA, dB)
     if workspace is None:
+        need = _workspace_bytes_cached(rows, D, G, io, x.device.index or 0)
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    elif (workspace.dtype != torch.uint8 or not workspace.is_contiguous() or workspace.device != x.device
+          or workspace.dim() != 1):
+        raise ValueError("workspace must be a contiguous one-dimensional uint8 tensor on the device of x")
     st = grkan_bwd_raw(x.data_ptr(), dy.data_ptr(), A.data_ptr(), B.data_ptr(), dx.data_ptr(),
-                       dA.data_ptr(), dB.data_ptr(), workspace.data_ptr(),
-                       workspace.numel() * workspace.element_size(), rows, D, G, io, _stream_ptr(stream),
-                       int(A.shape[1]) - 1, int(B.shape[1]))
+                       dA.data_ptr(), dB.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                       rows, D, G, io, _stream_ptr(stream), int(A.shape[1]) - 1, int(B.shape[1]))
     if st:
         raise GrkanError(st, "grkan_bwd")
     return dx, dA, dB

@@ -24,6 +24,7 @@
 // shape, alignment and device, so dA / dB are bit-identical from run to run.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdlib>
 #include <mutex>
 #include <tuple>
@@ -761,14 +762,20 @@ static bool device_info(int *dev_out, DeviceInfo *out)
     return true;
 }
 
-static int env_int(const char *name, int fallback)
+// Experiment overrides of the persistent grid sizes (workgroups per compute
+// unit; 0 = the built-in choice).  The two environment variables are read once,
+// when the library is loaded; grkan_tuning_override replaces them at run time.
+static int env_int(const char *name)
 {
     const char *s = std::getenv(name);
     if (!s || !*s)
-        return fallback;
+        return 0;
     const int v = std::atoi(s);
-    return v > 0 ? v : fallback;
+    return v > 0 ? v : 0;
 }
+
+static std::atomic<int> g_fwd_wg_per_cu{env_int("GRKAN_FWD_WG_PER_CU")};
+static std::atomic<int> g_bwd_wg_per_cu{env_int("GRKAN_BWD_WG_PER_CU")};
 
 static int32_t common_alignment(std::initializer_list<const void *> ptrs)
 {
@@ -910,7 +917,7 @@ static int resident_wg_per_cu(const void *kernel, int dev)
 // that sweeps whole rows as one stream - no column blocks - measured best at 3).  The bfloat16 backward pass moves half the
 // bytes for the same arithmetic and is bound by the vector ALU instead: it
 // takes every wave slot it can get (requests are clamped to the kernel's real
-// occupancy).  The environment variables override both walks for experiments.
+// occupancy).  The overrides above apply to both walks.
 struct Want {
     int group_walk;
     int flat_walk;
@@ -918,13 +925,13 @@ struct Want {
 
 static Want fwd_want(grkan_dtype_t)
 {
-    const int e = env_int("GRKAN_FWD_WG_PER_CU", 0);
+    const int e = g_fwd_wg_per_cu.load(std::memory_order_relaxed);
     return e ? Want{e, e} : Want{4, 4};
 }
 
 static Want bwd_want(grkan_dtype_t io)
 {
-    const int e = env_int("GRKAN_BWD_WG_PER_CU", 0);
+    const int e = g_bwd_wg_per_cu.load(std::memory_order_relaxed);
     if (e)
         return Want{e, e};
     return io == GRKAN_F32 ? Want{2, 3} : Want{8, 8}; // both 16-bit formats are ALU-bound
@@ -1013,6 +1020,12 @@ extern "C" size_t grkan_bwd_workspace_bytes(int64_t rows, int32_t D, int32_t G, 
         }
     }
     return need;
+}
+
+extern "C" void grkan_tuning_override(int32_t fwd_wg_per_cu, int32_t bwd_wg_per_cu)
+{
+    g_fwd_wg_per_cu.store(fwd_wg_per_cu > 0 ? fwd_wg_per_cu : 0, std::memory_order_relaxed);
+    g_bwd_wg_per_cu.store(bwd_wg_per_cu > 0 ? bwd_wg_per_cu : 0, std::memory_order_relaxed);
 }
 
 extern "C" grkan_status_t grkan_device_query(int32_t *out)

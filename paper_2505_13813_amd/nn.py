@@ -35,6 +35,22 @@ M_DEGREE = binding.M_DEGREE
 N_DEGREE = binding.N_DEGREE
 
 
+_workspaces = {}
+
+
+def _workspace(x, rows: int, D: int, G: int) -> torch.Tensor:
+    """One backward workspace per (device, stream), grown on demand.  Calls on one
+    stream run one after the other, so they can share it; the workspace's
+    contents mean nothing between calls."""
+    need = binding._workspace_bytes_cached(rows, D, G, binding._io_of(x), x.device.index or 0)
+    key = (x.device.index or 0, torch.cuda.current_stream(x.device).cuda_stream)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < need:
+        ws = torch.empty(max(need, 1 << 16), dtype=torch.uint8, device=x.device)
+        _workspaces[key] = ws
+    return ws
+
+
 class GroupRationalFunction(torch.autograd.Function):
     """y = F(x) group-wise; backward through grkan_bwd (nothing but x, A, B is saved)."""
 
@@ -49,7 +65,9 @@ class GroupRationalFunction(torch.autograd.Function):
     @staticmethod
     def backward(ctx, dy):
         x, A, B = ctx.saved_tensors
-        dx, dA, dB = binding.grkan_bwd(x, dy.contiguous(), A, B)
+        D = int(x.shape[-1])
+        ws = _workspace(x, int(x.numel() // D) if D else 0, D, int(A.shape[0]))
+        dx, dA, dB = binding.grkan_bwd(x, dy.contiguous(), A, B, workspace=ws)
         return dx, dA, dB
 
 

@@ -23,7 +23,8 @@ def declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for n in ("grkan_fwd", "grkan_bwd", "grkan_bwd_workspace_bytes", "grkan_plan",
-              "grkan_plan_cover_errors", "grkan_status_string", "grkan_alg1_bwd"):
+              "grkan_plan_cover_errors", "grkan_status_string", "grkan_alg1_bwd",
+              "grkan_tuning_override"):
         assert n in names
 
 

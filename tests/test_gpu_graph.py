@@ -23,7 +23,7 @@ def test_step_captured_in_a_graph_replays_bit_identically(config, tensors, dtype
     for t in tensors:
         case = grkan_inputs.make_case(config, t, dtype=dtype, rows=2048 if config != "tiny" else None)
         dev = to_device(case)
-        io = grkan.GRKAN_F32 if dtype == "f32" else grkan.GRKAN_BF16
+        io = {"f32": grkan.GRKAN_F32, "bf16": grkan.GRKAN_BF16, "f16": grkan.GRKAN_F16}[dtype]
         ws = torch.empty(grkan.grkan_bwd_workspace_bytes(case["rows"], case["D"], case["G"], io), dtype=torch.uint8,
                          device="cuda:0")
         out = dict(y=torch.empty_like(dev["x"]), dx=torch.empty_like(dev["x"]), dA=torch.empty_like(dev["A"]),

@@ -4,7 +4,8 @@ import numpy as np
 import pytest
 
 import grkan_inputs
-from parity_util import TOL, assert_parity, errors, run_gpu, run_oracle, to_device, to_host
+from parity_util import (ABS_FLOOR, TOL, assert_parity, format_stats, plain_stats, run_gpu, run_oracle,
+                         to_device, to_host)
 
 pytestmark = pytest.mark.gpu
 
@@ -83,21 +84,25 @@ def test_shapes_elementwise_other_degrees(oracle, rows, D, G, m, n, dtype):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("D,G", [(768, 8), (192, 8)])  # group walk / flat walk
-def test_every_trip_count_of_the_streaming_loop(oracle, monkeypatch, dtype, D, G):
+def test_every_trip_count_of_the_streaming_loop(oracle, dtype, D, G):
     """The streaming loop handles two chunks per trip and finishes with one or two
     more.  With one workgroup per compute unit and these sizes the waves make
     between one and six visits, odd and even, so every exit of the loop is
-    compared element by element (the large configurations only sample y and dx)."""
-    monkeypatch.setenv("GRKAN_FWD_WG_PER_CU", "1")
-    monkeypatch.setenv("GRKAN_BWD_WG_PER_CU", "1")
-    vec = 4 if dtype == "f32" else 8
-    per_pass = 256 * 4 * 64 * vec  # elements one pass of a 256-workgroup grid covers
-    for k, visits in enumerate((1.0, 1.5, 2.0, 2.6, 3.0, 3.7, 4.2, 5.0, 5.5)):
-        rows = int(visits * per_pass / D) + k
-        case = custom_case(9000 + k, rows, D, G, dtype)
-        gpu = run_gpu(case)
-        ref = run_oracle(oracle, case, threads=8)
-        assert_parity(gpu, ref, dtype, label="%dx%d G=%d %s (%.1f visits)" % (rows, D, G, dtype, visits))
+    compared element by element at sizes that take seconds."""
+    import paper_2505_13813_amd as grkan
+
+    grkan.tuning_override(1, 1)
+    try:
+        vec = 4 if dtype == "f32" else 8
+        per_pass = 256 * 4 * 64 * vec  # elements one pass of a 256-workgroup grid covers
+        for k, visits in enumerate((1.0, 1.5, 2.0, 2.6, 3.0, 3.7, 4.2, 5.0, 5.5)):
+            rows = int(visits * per_pass / D) + k
+            case = custom_case(9000 + k, rows, D, G, dtype)
+            gpu = run_gpu(case)
+            ref = run_oracle(oracle, case, threads=8)
+            assert_parity(gpu, ref, dtype, label="%dx%d G=%d %s (%.1f visits)" % (rows, D, G, dtype, visits))
+    finally:
+        grkan.tuning_override(0, 0)
 
 
 @pytest.mark.parametrize("dtype,offset", [("f32", 1), ("f32", 2), ("bf16", 1), ("bf16", 2), ("bf16", 4),
@@ -205,12 +210,15 @@ def test_empty_input():
     assert torch.count_nonzero(dA).item() == 0 and torch.count_nonzero(dB).item() == 0
 
 
-def test_outputs_may_alias_inputs(oracle):
+@pytest.mark.parametrize("rows,dtype", [(200, "f32"), (9000, "f32"), (9000, "bf16")])
+def test_outputs_may_alias_inputs(oracle, rows, dtype):
+    """y over x, dx over dy, dx over x.  The larger cases make every wave stream several chunks, so
+    the prefetch of the next chunk runs ahead of the aliased stores of the current one."""
     import torch
 
     import paper_2505_13813_amd as grkan
 
-    case = custom_case(8, 200, 768, 8)
+    case = custom_case(8, rows, 768, 8, dtype)
     dev = to_device(case)
     ref = run_oracle(oracle, case, threads=4)
     xa = dev["x"].clone()
@@ -220,7 +228,16 @@ def test_outputs_may_alias_inputs(oracle):
     grkan.grkan_bwd(dev["x"], dya, dev["A"], dev["B"], out=(dya, dA, dB))  # dx over dy
     torch.cuda.synchronize()
     gpu = dict(y=to_host(xa), dx=to_host(dya), dA=to_host(dA), dB=to_host(dB))
-    assert_parity(gpu, ref, "f32", label="aliased")
+    assert_parity(gpu, ref, dtype, label="aliased")
+    xb = dev["x"].clone()
+    dA2, dB2 = torch.empty_like(dev["A"]), torch.empty_like(dev["B"])
+    grkan.grkan_bwd(xb, dev["dy"], dev["A"], dev["B"], out=(xb, dA2, dB2))  # dx over x
+    torch.cuda.synchronize()
+    gpu2 = dict(y=gpu["y"], dx=to_host(xb), dA=to_host(dA2), dB=to_host(dB2))
+    assert_parity(gpu2, ref, dtype, label="dx over x")
+    # the same launch geometry and arithmetic whether or not the buffers alias
+    assert np.array_equal(gpu2["dx"], gpu["dx"]) and np.array_equal(gpu2["dA"], gpu["dA"])
+    assert np.array_equal(gpu2["dB"], gpu["dB"])
 
 
 def test_errors_from_the_device_side_checks():
@@ -296,8 +313,8 @@ def full_case(config, tensor, dtype, G, m=5, n=4):
 
 @pytest.mark.parametrize("config,tensor,dtype,G", FULL)
 def test_full_size_configuration(oracle, threads, config, tensor, dtype, G):
-    """At the bench's sizes and launch configuration: dA / dB against the oracle
-    over the whole array, y / dx on sampled rows (first, last, and random)."""
+    """At the bench's sizes and launch configuration: every element of y and dx
+    and every entry of dA / dB against the oracle."""
     check_full_size(oracle, threads, full_case(config, tensor, dtype, G))
 
 
@@ -307,25 +324,52 @@ def test_full_size_other_degrees(oracle, threads, config, tensor, dtype, G, m, n
 
 
 def check_full_size(oracle, threads, case):
+    """Every element of y and dx and every entry of dA and dB against the oracle,
+    in row blocks so that the float64 temporaries stay bounded."""
     config, tensor, dtype, G = case["config"], case["tensor"], case["dtype"], case["G"]
-    gpu = run_gpu(case)
-    rows = case["rows"]
-    rng = np.random.default_rng(99)
-    pick = np.unique(np.concatenate([np.arange(0, 8), np.arange(rows - 8, rows), rng.integers(0, rows, 240)]))
-    ref_s = run_oracle(oracle, case, threads=threads, rows=pick)
-    err = errors(gpu, dict(y=ref_s["y"], dx=ref_s["dx"], Sy=ref_s["Sy"], Sdx=ref_s["Sdx"]), rows=pick, dtype=dtype)
-    assert err["y"] <= TOL[dtype]["y"], err
-    assert err["dx"] <= TOL[dtype]["dx"], err
+    dev = to_device(case)
+    import torch
 
+    import paper_2505_13813_amd as grkan
+
+    y_d = grkan.grkan_fwd(dev["x"], dev["A"], dev["B"])
+    dx_d, dA_d, dB_d = grkan.grkan_bwd(dev["x"], dev["dy"], dev["A"], dev["B"])
+    torch.cuda.synchronize()
+    y_g = y_d.to(torch.float32).cpu().numpy()
+    dx_g = dx_d.to(torch.float32).cpu().numpy()
+    gpu = dict(dA=to_host(dA_d), dB=to_host(dB_d))
+    del dev, y_d, dx_d
+
+    rows = case["rows"]
+    A, B = case["A"].astype(np.float64), case["B"].astype(np.float64)
     x = case["x"].astype(np.float64)
     dy = case["dy"].astype(np.float64)
-    A, B = case["A"].astype(np.float64), case["B"].astype(np.float64)
-    _, dA, dB = oracle.bwd(x, dy, A, B, threads=threads)
-    _, _, RA, RB = oracle.scales(x, dy, A, B, threads=threads)
+    y = oracle.fwd(x, A, B, threads=threads)
+    dx, dA, dB = oracle.bwd(x, dy, A, B, threads=threads)
+    Sy, Sdx, RA, RB = oracle.scales(x, dy, A, B, threads=threads)
+    del x, dy
+
+    floor = ABS_FLOOR[dtype]
+    tiny = np.finfo(np.float64).tiny
+    err = dict(y=0.0, dx=0.0)
+    block = 4096
+    for r0 in range(0, rows, block):
+        sl = slice(r0, min(rows, r0 + block))
+        for name, g, r, s in (("y", y_g, y, Sy), ("dx", dx_g, dx, Sdx)):
+            gb = g[sl].astype(np.float64)
+            assert np.all(np.isfinite(gb)), "%s has non-finite values in rows %d.." % (name, r0)
+            e = np.maximum(np.abs(gb - r[sl]) - floor, 0.0) / np.maximum(np.maximum(np.abs(r[sl]), s[sl]), tiny)
+            err[name] = max(err[name], float(e.max()))
     eA = float(np.max(np.abs(gpu["dA"] - dA) / np.maximum(np.abs(dA), RA)))
     eB = float(np.max(np.abs(gpu["dB"] - dB) / np.maximum(np.abs(dB), RB)))
-    print(config, tensor, dtype, "G=%d" % G, "(%d,%d)" % (case["m"], case["n"]),
-          "y %.2e dx %.2e dA %.2e dB %.2e" % (err["y"], err["dx"], eA, eB))
+    print()
+    print(config, tensor, dtype, "G=%d" % G, "(%d,%d)" % (case["m"], case["n"]), "all %d elements" % y.size)
+    print("  " + format_stats("y ", err["y"], plain_stats(y_g, y)))
+    print("  " + format_stats("dx", err["dx"], plain_stats(dx_g, dx)))
+    print("  " + format_stats("dA", eA, plain_stats(gpu["dA"], dA)))
+    print("  " + format_stats("dB", eB, plain_stats(gpu["dB"], dB)))
+    assert err["y"] <= TOL[dtype]["y"], err
+    assert err["dx"] <= TOL[dtype]["dx"], err
     assert np.all(np.isfinite(gpu["dA"])) and np.all(np.isfinite(gpu["dB"]))
     assert eA <= TOL[dtype]["dA"] and eB <= TOL[dtype]["dB"], (eA, eB)
     # plain relative error where the sums are well conditioned
