@@ -52,8 +52,9 @@ def test_offsets_beyond_4_gib(oracle, G):
     dx_ref, _, _ = oracle.bwd(xs, dys, A64, B64, threads=threads)
     Sy, Sdx, _, _ = oracle.scales(xs, dys, A64, B64, threads=threads)
     y_s, dx_s = y[idx].cpu().numpy(), dx[idx].cpu().numpy()
-    ey = np.max(np.abs(y_s - y_ref) / np.maximum(np.abs(y_ref), Sy))
-    edx = np.max(np.abs(dx_s - dx_ref) / np.maximum(np.abs(dx_ref), Sdx))
+    tiny = np.finfo(np.float64).tiny  # an upstream gradient drawn as exactly 0 gives dx = Sdx = 0
+    ey = np.max(np.abs(y_s - y_ref) / np.maximum(np.maximum(np.abs(y_ref), Sy), tiny))
+    edx = np.max(np.abs(dx_s - dx_ref) / np.maximum(np.maximum(np.abs(dx_ref), Sdx), tiny))
     print()
     print("  " + format_stats("y  (%d rows)" % len(pick), ey, plain_stats(y_s, y_ref)))
     print("  " + format_stats("dx (%d rows)" % len(pick), edx, plain_stats(dx_s, dx_ref)))
