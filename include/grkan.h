@@ -57,7 +57,8 @@ typedef enum {
     GRKAN_ERR_WORKSPACE = 5, /* workspace missing or smaller than required */
     GRKAN_ERR_DTYPE = 6,     /* unknown grkan_dtype_t */
     GRKAN_ERR_LAUNCH = 7,    /* the HIP runtime rejected a launch or query */
-    GRKAN_ERR_UNSUPPORTED = 8 /* shape outside what the kernels index (see grkan_plan) */
+    GRKAN_ERR_UNSUPPORTED = 8, /* shape outside what the kernels index (see grkan_plan) */
+    GRKAN_ERR_SCRATCH_LIMIT = 9 /* grkan_bwd_noalloc: the shape needs more workspace than the built-in scratch */
 } grkan_status_t;
 
 /* Human-readable name of a status; never NULL; static storage. */
@@ -173,6 +174,32 @@ grkan_status_t grkan_bwd(const void *x, const void *dy, const float *A, const fl
                          void *workspace, size_t workspace_bytes,
                          int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
                          grkan_dtype_t io, void *hip_stream);
+
+/*
+ * grkan_bwd for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and kernels as grkan_bwd (bit-identical
+ * outputs), minus the workspace: the workspace rows live in a fixed array of
+ * GRKAN_NOALLOC_SCRATCH_BYTES (4 MiB) of device memory that belongs to the
+ * library (one copy on every GPU it runs on, held until the process ends).
+ * The call allocates and frees nothing.
+ *
+ *   - A shape whose workspace (grkan_bwd_workspace_bytes: G * rows per group *
+ *     (m+1+n) * 4 bytes; 20 KB at the paper's KAT-B shape, 0.2 MB for 64 groups)
+ *     exceeds the array returns GRKAN_ERR_SCRATCH_LIMIT and enqueues nothing.
+ *   - Every call on one GPU uses that GPU's one array: calls whose kernels can
+ *     overlap on a GPU (different streams, several host threads) race on it and
+ *     give wrong dA / dB.  Calls on one stream are safe.  The array keeps the
+ *     last call's rows; nothing in it has to start at zero, because stage 1
+ *     writes every row stage 2 reads.
+ *   - The first call on a device looks the array's address up (no allocation);
+ *     make that call outside a graph capture.
+ */
+#define GRKAN_NOALLOC_SCRATCH_BYTES ((size_t)4 << 20)
+grkan_status_t grkan_bwd_noalloc(const void *x, const void *dy, const float *A, const float *B,
+                                 void *dx, float *dA, float *dB,
+                                 int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
+                                 grkan_dtype_t io, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     device_query,
     grkan_alg1_bwd,
     grkan_bwd,
+    grkan_bwd_noalloc,
     grkan_bwd_raw,
     grkan_bwd_workspace_bytes,
     grkan_fwd,

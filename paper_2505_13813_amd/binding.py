@@ -85,6 +85,8 @@ def load_library():
     lib.grkan_fwd.restype = ctypes.c_int
     lib.grkan_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i64, i32, i32, i32, i32, ctypes.c_int, vp]
     lib.grkan_bwd.restype = ctypes.c_int
+    lib.grkan_bwd_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, ctypes.c_int, vp]
+    lib.grkan_bwd_noalloc.restype = ctypes.c_int
     lib.grkan_alg1_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, vp]
     lib.grkan_alg1_bwd.restype = ctypes.c_int
     _lib = lib
@@ -250,6 +252,26 @@ def grkan_bwd(x, dy, A, B, workspace: Optional["torch.Tensor"] = None, out=None,
                        rows, D, G, io, _stream_ptr(stream), int(A.shape[1]) - 1, int(B.shape[1]))
     if st:
         raise GrkanError(st, "grkan_bwd")
+    return dx, dA, dB
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20
+
+
+def grkan_bwd_noalloc(x, dy, A, B, out, stream=None):
+    """grkan_bwd without a workspace argument and without any allocation: the
+    caller passes every output (`out` = (dx, dA, dB)); the workspace rows live in
+    the library's fixed 4 MiB device array.  Calls that overlap on one GPU race."""
+    rows, D, G = _check(x, A, B)
+    if dy.shape != x.shape or dy.dtype != x.dtype or not dy.is_contiguous() or dy.device != x.device:
+        raise ValueError("dy must match x")
+    dx, dA, dB = out
+    _check_bwd_outputs(x, A, B, dx, dA, dB)
+    st = int(load_library().grkan_bwd_noalloc(x.data_ptr(), dy.data_ptr(), A.data_ptr(), B.data_ptr(), dx.data_ptr(),
+                                              dA.data_ptr(), dB.data_ptr(), rows, D, G, int(A.shape[1]) - 1,
+                                              int(B.shape[1]), _io_of(x), _stream_ptr(stream)))
+    if st:
+        raise GrkanError(st, "grkan_bwd_noalloc")
     return dx, dA, dB
 
 

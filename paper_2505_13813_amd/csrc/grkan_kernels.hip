@@ -1085,11 +1085,40 @@ extern "C" grkan_status_t grkan_fwd(const void *x, const float *A, const float *
     return e == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
 }
 
-extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *A, const float *B,
-                                    void *dx, float *dA, float *dB,
-                                    void *workspace, size_t workspace_bytes,
-                                    int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
-                                    grkan_dtype_t io, void *hip_stream)
+namespace grkan {
+
+// Scratch of the allocation-free entry point: the workspace rows of stage 1,
+// in a fixed array in device memory (one copy per GPU the library runs on, held
+// until the process ends).  In host code the array's name is only a handle for
+// the symbol; its address on a device comes from hipGetSymbolAddress, once per
+// device, and only that pointer is ever handed to a kernel.
+constexpr size_t kScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[64]; // per device, filled on the first call there
+
+// `dev` must be the current device.
+static grkan_status_t scratch_of_device(int dev, void **out)
+{
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr)
+            return GRKAN_ERR_LAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return GRKAN_OK;
+}
+
+// Both backward entry points.  own_scratch: the workspace is the library's
+// fixed array (then `workspace` / `workspace_bytes` are ignored).
+static grkan_status_t bwd_impl(const void *x, const void *dy, const float *A, const float *B,
+                               void *dx, float *dA, float *dB,
+                               void *workspace, size_t workspace_bytes, bool own_scratch,
+                               int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
+                               grkan_dtype_t io, void *hip_stream)
 {
     const DegreeOps *ops = nullptr;
     grkan_status_t st = check_common(rows, D, G, m, n, io, &ops);
@@ -1115,8 +1144,16 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
     if (st != GRKAN_OK)
         return st;
     const size_t need = workspace_for(pl, G, m + 1 + n);
-    if (need > 0 && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0))
+    if (own_scratch) {
+        if (need > kScratchBytes)
+            return GRKAN_ERR_SCRATCH_LIMIT;
+        st = scratch_of_device(dev, &workspace);
+        if (st != GRKAN_OK)
+            return st;
+    } else if (need > 0 &&
+               (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)) {
         return GRKAN_ERR_WORKSPACE;
+    }
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     a.x = static_cast<const char *>(x);
@@ -1131,11 +1168,32 @@ extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *
         if (hipLaunchKernel(kernel, dim3(pl.grid), dim3(kThreadsPerWg), args, 0, stream) != hipSuccess)
             return GRKAN_ERR_LAUNCH;
     }
-    // with no rows there are no workspace rows and stage 2 writes zeros
+    // Stage 1 writes every workspace row stage 2 reads (one per workgroup and group, zeros included),
+    // so nothing has to be cleared beforehand; with no rows there are no workspace rows and stage 2
+    // writes zeros.
     const float *partial = a.partial;
     int32_t rows_per_group = pl.partials_per_group;
     void *args2[] = {&partial, &rows_per_group, &dA, &dB};
     const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(ops->stage2), dim3(G),
                                          dim3(stage2_threads(rows_per_group)), args2, 0, stream);
     return e == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
+}
+
+} // namespace grkan
+
+extern "C" grkan_status_t grkan_bwd(const void *x, const void *dy, const float *A, const float *B,
+                                    void *dx, float *dA, float *dB,
+                                    void *workspace, size_t workspace_bytes,
+                                    int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
+                                    grkan_dtype_t io, void *hip_stream)
+{
+    return bwd_impl(x, dy, A, B, dx, dA, dB, workspace, workspace_bytes, false, rows, D, G, m, n, io, hip_stream);
+}
+
+extern "C" grkan_status_t grkan_bwd_noalloc(const void *x, const void *dy, const float *A, const float *B,
+                                            void *dx, float *dA, float *dB,
+                                            int64_t rows, int32_t D, int32_t G, int32_t m, int32_t n,
+                                            grkan_dtype_t io, void *hip_stream)
+{
+    return bwd_impl(x, dy, A, B, dx, dA, dB, nullptr, 0, true, rows, D, G, m, n, io, hip_stream);
 }

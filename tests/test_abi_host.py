@@ -23,7 +23,7 @@ def declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for n in ("grkan_fwd", "grkan_bwd", "grkan_bwd_workspace_bytes", "grkan_plan",
-              "grkan_plan_cover_errors", "grkan_status_string", "grkan_alg1_bwd",
+              "grkan_plan_cover_errors", "grkan_status_string", "grkan_alg1_bwd", "grkan_bwd_noalloc",
               "grkan_tuning_override"):
         assert n in names
 
@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     seen = set()
-    for code in range(0, 9):
+    for code in range(0, 10):
         s = grkan.status_string(code)
         assert s and s not in seen
         seen.add(s)
