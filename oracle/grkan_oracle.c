@@ -23,6 +23,9 @@
  * groups are 0-based contiguous channel blocks; B[g][0] multiplies x^1 (there
  * is no b_0); dA and dB are overwritten with the sums.
  *
+ * Further down: the GR-KAN layer itself, out = W F(x) (Eq. "GR_KAN"), and its
+ * backward pass by the chain rule.
+ *
  * Layout: x, dy, y, dx are row-major [rows][D]; A is [G][m+1], B is [G][n].
  * The coefficient sums use Neumaier-compensated double accumulation.
  *
@@ -303,6 +306,122 @@ int grkan_oracle_scales(const double *x, const double *dy, const double *A, cons
     }
     free(sq);
     return 0;
+}
+
+/*
+ * GR-KAN layer (Sec. "Kolmogorov-Arnold Transformer", Eq. "GR_KAN"): the
+ * group-wise rational function followed by the weighted summation,
+ *
+ *   out[r][o] = sum_c W[o][c] * F_{g(c)}(x[r][c])   (+ bias[o] if bias != NULL)
+ *
+ * W is [D_out][D_in] row-major (the paper's W in R^{d_out x d_in}); the
+ * equation has no bias term, which is an optional addition of this build
+ * (bias == NULL gives the equation itself).  Plain loops, double precision,
+ * Neumaier-compensated sum over c.
+ *
+ * round_operand: 0 = the definition.  1 = F is rounded to bfloat16 (8
+ * significant bits, round to nearest, ties to even) before it is multiplied,
+ * which is the quantised operand a bfloat16 matrix unit is fed; used by the
+ * parity tests to check the contraction apart from that rounding.
+ */
+static double round_to_bf16(double v)
+{
+    if (v == 0.0 || !isfinite(v))
+        return v;
+    int e;
+    const double mant = frexp(v, &e);    /* v = mant * 2^e, 0.5 <= |mant| < 1 */
+    return ldexp(rint(ldexp(mant, 8)), e - 8); /* 8 significant bits; rint rounds ties to even */
+}
+
+int grkan_oracle_linear_fwd(const double *x, const double *A, const double *B, const double *W,
+                            const double *bias, double *out,
+                            int64_t rows, int D_in, int D_out, int G, int m, int n,
+                            int round_operand, int threads)
+{
+    int rc = check_args(rows, D_in, G, m, n);
+    if (rc)
+        return rc;
+    if (D_out <= 0)
+        return 2;
+    const int dg = D_in / G;
+    threads = pick_threads(threads, rows);
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads) if (threads > 1)
+#endif
+    {
+        double *f = (double *)malloc((size_t)D_in * sizeof(double));
+#ifdef _OPENMP
+#pragma omp for schedule(static)
+#endif
+        for (int64_t r = 0; r < rows; ++r) {
+            if (!f)
+                continue;
+            for (int c = 0; c < D_in; ++c) {
+                const int g = c / dg;
+                elem_t e;
+                eval_elem(x[r * D_in + c], A + (size_t)g * (m + 1), m, B + (size_t)g * n, n, &e);
+                const double v = e.P / e.Q;
+                f[c] = round_operand ? round_to_bf16(v) : v;
+            }
+            for (int o = 0; o < D_out; ++o) {
+                nacc_t acc = {0.0, 0.0};
+                for (int c = 0; c < D_in; ++c)
+                    nacc_add(&acc, W[(size_t)o * D_in + c] * f[c]);
+                out[r * D_out + o] = nacc_value(&acc) + (bias ? bias[o] : 0.0);
+            }
+        }
+        free(f);
+    }
+    return 0;
+}
+
+/*
+ * Backward of the GR-KAN layer for an upstream gradient dOut [rows][D_out]
+ * (chain rule through Eq. "GR_KAN", then Eq. "grad_x", "grad_a", "grad_b",
+ * "accum", "accum2" with dy = dF):
+ *
+ *   dF[r][c]   = sum_o dOut[r][o] * W[o][c]
+ *   dW[o][c]   = sum_r dOut[r][o] * F_{g(c)}(x[r][c])
+ *   dbias[o]   = sum_r dOut[r][o]
+ *   dx, dA, dB = backward of the rational function for the upstream gradient dF
+ *
+ * dF is returned too (the tests use it).  Sequential; small cases only.
+ */
+int grkan_oracle_linear_bwd(const double *x, const double *dOut, const double *A, const double *B,
+                            const double *W, double *dF, double *dx, double *dA, double *dB,
+                            double *dW, double *dbias,
+                            int64_t rows, int D_in, int D_out, int G, int m, int n)
+{
+    int rc = check_args(rows, D_in, G, m, n);
+    if (rc)
+        return rc;
+    if (D_out <= 0)
+        return 2;
+    const int dg = D_in / G;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int c = 0; c < D_in; ++c) {
+            nacc_t acc = {0.0, 0.0};
+            for (int o = 0; o < D_out; ++o)
+                nacc_add(&acc, dOut[r * D_out + o] * W[(size_t)o * D_in + c]);
+            dF[r * D_in + c] = nacc_value(&acc);
+        }
+    for (int o = 0; o < D_out; ++o) {
+        nacc_t b = {0.0, 0.0};
+        for (int64_t r = 0; r < rows; ++r)
+            nacc_add(&b, dOut[r * D_out + o]);
+        dbias[o] = nacc_value(&b);
+        for (int c = 0; c < D_in; ++c) {
+            const int g = c / dg;
+            nacc_t acc = {0.0, 0.0};
+            for (int64_t r = 0; r < rows; ++r) {
+                elem_t e;
+                eval_elem(x[r * D_in + c], A + (size_t)g * (m + 1), m, B + (size_t)g * n, n, &e);
+                nacc_add(&acc, dOut[r * D_out + o] * (e.P / e.Q));
+            }
+            dW[(size_t)o * D_in + c] = nacc_value(&acc);
+        }
+    }
+    return grkan_oracle_bwd(x, dF, A, B, dx, dA, dB, rows, D_in, G, m, n, 1);
 }
 
 /* Number of OpenMP threads the oracle would use when asked for `threads`. */

@@ -50,6 +50,10 @@ def _load():
         lib.grkan_oracle_bwd.restype = i32
         lib.grkan_oracle_scales.argtypes = [dp, dp, dp, dp, dp, dp, dp, dp, i64, i32, i32, i32, i32, i32]
         lib.grkan_oracle_scales.restype = i32
+        lib.grkan_oracle_linear_fwd.argtypes = [dp, dp, dp, dp, dp, dp, i64, i32, i32, i32, i32, i32, i32, i32]
+        lib.grkan_oracle_linear_fwd.restype = i32
+        lib.grkan_oracle_linear_bwd.argtypes = [dp] * 11 + [i64, i32, i32, i32, i32, i32]
+        lib.grkan_oracle_linear_bwd.restype = i32
         lib.grkan_oracle_max_threads.argtypes = []
         lib.grkan_oracle_max_threads.restype = i32
         _lib = lib
@@ -122,3 +126,68 @@ def scales(x, dy, A, B, threads: int = 1):
     if rc:
         raise ValueError("grkan_oracle_scales failed with code %d" % rc)
     return Sy, Sdx, RA, RB
+
+
+# ---------------------------------------------------------------- GR-KAN layer, out = W F(x) (Eq. "GR_KAN")
+def _linear_shapes(x, A, B, W):
+    rows, D_in, G, m, n = _shapes(x, A, B)
+    if W.ndim != 2 or W.shape[1] != D_in:
+        raise ValueError("W must be [D_out, D_in]")
+    return rows, D_in, int(W.shape[0]), G, m, n
+
+
+def linear_fwd(x, A, B, W, bias=None, round_operand: bool = False, threads: int = 1) -> np.ndarray:
+    """out[r, o] = sum_c W[o, c] F_{g(c)}(x[r, c]) (+ bias[o]): plain loops in C, fp64.
+    round_operand=True rounds F to bfloat16 (nearest even) before the product."""
+    x, A, B, W = _f64(x), _f64(A), _f64(B), _f64(W)
+    rows, D_in, D_out, G, m, n = _linear_shapes(x, A, B, W)
+    bias = _f64(bias) if bias is not None else None
+    if bias is not None and bias.shape != (D_out,):
+        raise ValueError("bias must be [D_out]")
+    out = np.empty(x.shape[:-1] + (D_out,), dtype=np.float64)
+    rc = _load().grkan_oracle_linear_fwd(_ptr(x), _ptr(A), _ptr(B), _ptr(W), _ptr(bias), _ptr(out),
+                                         rows, D_in, D_out, G, m, n, 1 if round_operand else 0, threads)
+    if rc:
+        raise ValueError("grkan_oracle_linear_fwd failed with code %d" % rc)
+    return out
+
+
+def linear_fwd_matmul(x, A, B, W, bias=None, round_operand: bool = False, threads: int = 1) -> np.ndarray:
+    """The same result with the library matrix product as the summation step
+    (fwd, then numpy's fp64 matmul): for the full-size cases, where the plain
+    loops would take minutes.  The rounding of the operand, if asked for, is
+    numpy's own arithmetic here (not the C helper)."""
+    W = _f64(W)
+    y = fwd(x, A, B, threads=threads)
+    if round_operand:
+        mant, e = np.frexp(y)
+        y = np.ldexp(np.rint(np.ldexp(mant, 8)), e - 8)
+    out = y @ W.T
+    if bias is not None:
+        out += _f64(bias)
+    return out
+
+
+def linear_term_scale(x, A, B, W, threads: int = 1) -> np.ndarray:
+    """Root-sum-square of the summed terms, sqrt(sum_c (W[o, c] F(x[r, c]))^2):
+    the scale of the rounding error of the contraction, used by the parity
+    metric of the fused layer (not part of the method)."""
+    W = _f64(W)
+    y = fwd(x, A, B, threads=threads)
+    return np.sqrt((y * y) @ (W * W).T)
+
+
+def linear_bwd(x, dOut, A, B, W):
+    """dict(dF, dx, dA, dB, dW, dbias) of the GR-KAN layer by the chain rule; sequential, small cases."""
+    x, dOut, A, B, W = _f64(x), _f64(dOut), _f64(A), _f64(B), _f64(W)
+    rows, D_in, D_out, G, m, n = _linear_shapes(x, A, B, W)
+    if dOut.shape != x.shape[:-1] + (D_out,):
+        raise ValueError("dOut must be [rows, D_out]")
+    dF, dx = np.empty_like(x), np.empty_like(x)
+    dA, dB = np.empty((G, m + 1)), np.empty((G, n))
+    dW, dbias = np.empty_like(W), np.empty(D_out)
+    rc = _load().grkan_oracle_linear_bwd(_ptr(x), _ptr(dOut), _ptr(A), _ptr(B), _ptr(W), _ptr(dF), _ptr(dx),
+                                         _ptr(dA), _ptr(dB), _ptr(dW), _ptr(dbias), rows, D_in, D_out, G, m, n)
+    if rc:
+        raise ValueError("grkan_oracle_linear_bwd failed with code %d" % rc)
+    return dict(dF=dF, dx=dx, dA=dA, dB=dB, dW=dW, dbias=dbias)
