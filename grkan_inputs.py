@@ -84,9 +84,9 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def _streams(cfg: Config):
+def _streams(cfg: Config, extra: int = 0):
     ss = np.random.SeedSequence(1000 + cfg.index)
-    kids = ss.spawn(2 + 3 * len(cfg.tensors))
+    kids = ss.spawn(2 + 3 * len(cfg.tensors) + extra)
     return [np.random.Generator(np.random.PCG64(k)) for k in kids]
 
 
@@ -181,4 +181,42 @@ def upload(case: dict, device: str = "cuda:0") -> dict:
                 torch.bfloat16 if case["dtype"] == "bf16" else torch.float16)
         else:
             dev[k] = torch.from_numpy(np.ascontiguousarray(case[k])).to(device)
+    return dev
+
+
+def make_linear_case(config: str, tensor: Optional[str] = None, D_out: Optional[int] = None,
+                     rows: Optional[int] = None, bias: bool = True) -> dict:
+    """A GR-KAN layer out = W F(x) + bias at the paper's shapes, bfloat16 storage.
+
+    `tensor` names the layer's input among the config's tensors: "x1" feeds the
+    first linear layer of the MLP block (D_out = 4 D_in), "x2" the second
+    (D_out = D_in / 4); single-tensor configs default to D_out = D_in.  x, A, B
+    are those of make_case(dtype="bf16").  W ~ N(0, 1 / D_in) (the paper's
+    variance-preserving scale for an identity-like F), drawn from two further
+    child streams per tensor (after all of make_case's, so those are unchanged),
+    stored as bfloat16; bias ~ N(0, 0.1^2) float32.  Data only."""
+    case = make_case(config, tensor, dtype="bf16", rows=rows)
+    cfg = CONFIGS[config]
+    names = [t for t, _ in cfg.tensors]
+    ti = names.index(case["tensor"])
+    D_in = case["D"]
+    if D_out is None:
+        D_out = 4 * D_in if case["tensor"] == "x1" else (D_in // 4 if case["tensor"] == "x2" else D_in)
+    gens = _streams(cfg, extra=2 * len(cfg.tensors))
+    base = 2 + 3 * len(cfg.tensors)
+    W = gens[base + 2 * ti].standard_normal(size=(D_out, D_in), dtype=np.float32) / np.float32(np.sqrt(D_in))
+    Wb = round_to_bf16_bits(W)
+    case.update(D_in=D_in, D_out=int(D_out), W_bits=Wb, W=bf16_bits_to_f32(Wb))
+    case["bias"] = (gens[base + 2 * ti + 1].standard_normal(size=(D_out,), dtype=np.float32) * np.float32(0.1)
+                    if bias else None)
+    return case
+
+
+def upload_linear(case: dict, device: str = "cuda:0") -> dict:
+    """upload() plus W (bfloat16) and bias (float32 or None).  Data movement only."""
+    import torch
+
+    dev = upload(case, device)
+    dev["W"] = torch.from_numpy(np.ascontiguousarray(case["W_bits"]).view(np.int16)).to(device).view(torch.bfloat16)
+    dev["bias"] = torch.from_numpy(case["bias"]).to(device) if case.get("bias") is not None else None
     return dev

@@ -176,6 +176,37 @@ grkan_status_t grkan_bwd(const void *x, const void *dy, const float *A, const fl
                          grkan_dtype_t io, void *hip_stream);
 
 /*
+ * The GR-KAN layer in one kernel (Sec. "Kolmogorov-Arnold Transformer", Eq. "GR_KAN" with F of Eq. "pade"):
+ *
+ *     out[r, o] = sum_c W[o, c] * F_{g(c)}(x[r, c])  (+ bias[o]),   g(c) = c div d_g, d_g = D_in / G
+ *
+ * The rational function is evaluated in float32 on the way into the matrix
+ * cores, rounded to bfloat16 (nearest even) and multiplied with bfloat16 weights
+ * with float32 accumulation (v_mfma_f32_16x16x32_bf16); F(x) is never written
+ * to memory.  (The equation has no bias; bias == NULL gives the equation.)
+ *
+ *   x    DEVICE, bfloat16 [rows, D_in], contiguous, 16-byte aligned   (io must be GRKAN_BF16)
+ *   A, B DEVICE, float32 [G, m+1] / [G, n] as for grkan_fwd; (m, n) must be (5, 4)
+ *   W    DEVICE, bfloat16 [D_out, D_in] row-major (the paper's W in R^{d_out x d_in}), 16-byte aligned
+ *   bias DEVICE, float32 [D_out], 16-byte aligned, or NULL
+ *   out  DEVICE, [rows, D_out] of out_dtype (GRKAN_BF16: rounded to nearest even; GRKAN_F32), 16-byte
+ *        aligned; must not overlap x or W
+ *
+ * Shapes: D_in a multiple of 64, d_g a multiple of 32 and D_out a multiple of 4
+ * (every KAT-S fc2 / KAT-B shape of the paper's model table qualifies); anything else returns
+ * GRKAN_ERR_UNSUPPORTED and the caller runs grkan_fwd followed by its own
+ * matrix product.  Asynchronous on hip_stream, caller-owned memory, no
+ * workspace, results independent of the launch (fixed summation order per
+ * output).  The first call of a kernel variant on a device raises that kernel's
+ * dynamic-LDS limit (no allocation).
+ */
+grkan_status_t grkan_linear_fwd(const void *x, const float *A, const float *B, const void *W,
+                                const float *bias, void *out,
+                                int64_t rows, int32_t D_in, int32_t D_out, int32_t G,
+                                int32_t m, int32_t n, grkan_dtype_t io, grkan_dtype_t out_dtype,
+                                void *hip_stream);
+
+/*
  * grkan_bwd for callers that cannot allocate device memory or pass a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, results and kernels as grkan_bwd (bit-identical

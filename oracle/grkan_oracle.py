@@ -177,6 +177,19 @@ def linear_term_scale(x, A, B, W, threads: int = 1) -> np.ndarray:
     return np.sqrt((y * y) @ (W * W).T)
 
 
+def linear_largest_term(x, A, B, W, threads: int = 1) -> np.ndarray:
+    """max_c |W[o, c] F(x[r, c])| per output: the size of the one term whose
+    bfloat16 rounding can change an output most (used by the parity metric of the
+    fused layer; not part of the method).  rows * D_out * D_in operations in
+    numpy: small cases or a sample of rows."""
+    W = np.abs(_f64(W))
+    y = np.abs(fwd(x, A, B, threads=threads)).reshape(-1, W.shape[1])
+    out = np.zeros((y.shape[0], W.shape[0]))
+    for c in range(W.shape[1]):
+        np.maximum(out, y[:, c, None] * W[None, :, c], out=out)
+    return out.reshape(np.shape(x)[:-1] + (W.shape[0],))
+
+
 def linear_bwd(x, dOut, A, B, W):
     """dict(dF, dx, dA, dB, dW, dbias) of the GR-KAN layer by the chain rule; sequential, small cases."""
     x, dOut, A, B, W = _f64(x), _f64(dOut), _f64(A), _f64(B), _f64(W)

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     grkan_bwd_raw,
     grkan_bwd_workspace_bytes,
     grkan_fwd,
+    grkan_linear_fwd,
     grkan_fwd_raw,
     load_library,
     plan,

@@ -85,6 +85,8 @@ def load_library():
     lib.grkan_fwd.restype = ctypes.c_int
     lib.grkan_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, i64, i32, i32, i32, i32, ctypes.c_int, vp]
     lib.grkan_bwd.restype = ctypes.c_int
+    lib.grkan_linear_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_int, ctypes.c_int, vp]
+    lib.grkan_linear_fwd.restype = ctypes.c_int
     lib.grkan_bwd_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, ctypes.c_int, vp]
     lib.grkan_bwd_noalloc.restype = ctypes.c_int
     lib.grkan_alg1_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, vp]
@@ -253,6 +255,34 @@ def grkan_bwd(x, dy, A, B, workspace: Optional["torch.Tensor"] = None, out=None,
     if st:
         raise GrkanError(st, "grkan_bwd")
     return dx, dA, dB
+
+
+def grkan_linear_fwd(x, A, B, W, bias=None, out=None, out_dtype=None, stream=None):
+    """out = F(x) W^T (+ bias): the GR-KAN layer in one kernel (Eq. "GR_KAN").  x and W
+    bfloat16, bias float32 or None, out bfloat16 (default) or float32."""
+    import torch
+
+    rows, D_in, G = _check(x, A, B)
+    if x.dtype != torch.bfloat16 or W.dtype != torch.bfloat16:
+        raise TypeError("x and W must be bfloat16")
+    if W.dim() != 2 or W.shape[1] != D_in or not W.is_contiguous() or W.device != x.device:
+        raise ValueError("W must be a contiguous [D_out, D_in] tensor on the device of x")
+    D_out = int(W.shape[0])
+    if bias is not None and (bias.dtype != torch.float32 or bias.shape != (D_out,) or not bias.is_contiguous()
+                             or bias.device != x.device):
+        raise ValueError("bias must be a contiguous float32 [D_out] tensor on the device of x")
+    if out is None:
+        out = torch.empty(x.shape[:-1] + (D_out,), dtype=out_dtype or torch.bfloat16, device=x.device)
+    if (out.dtype not in (torch.bfloat16, torch.float32) or out.shape != x.shape[:-1] + (D_out,)
+            or not out.is_contiguous() or out.device != x.device):
+        raise ValueError("out must be a contiguous bfloat16 or float32 [..., D_out] tensor on the device of x")
+    st = int(load_library().grkan_linear_fwd(
+        x.data_ptr(), A.data_ptr(), B.data_ptr(), W.data_ptr(), bias.data_ptr() if bias is not None else None,
+        out.data_ptr(), rows, D_in, D_out, G, int(A.shape[1]) - 1, int(B.shape[1]), GRKAN_BF16,
+        GRKAN_BF16 if out.dtype == torch.bfloat16 else GRKAN_F32, _stream_ptr(stream)))
+    if st:
+        raise GrkanError(st, "grkan_linear_fwd")
+    return out
 
 
 NOALLOC_SCRATCH_BYTES = 4 << 20

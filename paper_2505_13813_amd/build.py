@@ -9,8 +9,9 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libgrkan.so"
-SOURCES = [CSRC / "grkan_kernels.hip", CSRC / "grkan_plan.cpp", CSRC / "grkan_alg1_baseline.hip"]
-HEADERS = [CSRC / "grkan_walk.h", CSRC / "grkan_plan.h", PKG.parent / "include" / "grkan.h",
+SOURCES = [CSRC / "grkan_kernels.hip", CSRC / "grkan_plan.cpp", CSRC / "grkan_alg1_baseline.hip",
+           CSRC / "grkan_linear.hip"]
+HEADERS = [CSRC / "grkan_walk.h", CSRC / "grkan_plan.h", CSRC / "grkan_elem.h", PKG.parent / "include" / "grkan.h",
            PKG.parent / "include" / "grkan_alg1.h"]
 
 # packed-fp32 code generation is switched off on purpose (hipcc flag, device side)

@@ -176,6 +176,17 @@ def test_l9_term_scale_is_the_root_sum_square_of_the_terms(oracle):
     assert np.all(np.abs(oracle.linear_fwd(x, A, B, W)) <= np.sqrt(12) * want * (1 + 1e-12))
 
 
+def test_l9b_largest_term(oracle):
+    x, A, B, W, _, _ = case(12, rows=4, D_in=12, D_out=5, G=3)
+    y = oracle.fwd(x, A, B)
+    want = np.array([[max(abs(W[o, c] * y[r, c]) for c in range(12)) for o in range(5)] for r in range(4)])
+    got = oracle.linear_largest_term(x, A, B, W)
+    np.testing.assert_allclose(got, want, rtol=1e-14)
+    # between the root-mean-square and the root-sum-square of the terms
+    R = oracle.linear_term_scale(x, A, B, W)
+    assert np.all(got <= R * (1 + 1e-12)) and np.all(got >= R / np.sqrt(12) * (1 - 1e-12))
+
+
 def test_linear_oracle_rejects_bad_shapes(oracle):
     x, A, B, W, bias, _ = case(11)
     with pytest.raises(ValueError):
