@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <type_traits>
 
 #include "../../include/grkan.h"
 #include "grkan_elem.h"
@@ -53,7 +54,7 @@ constexpr int kMT = 7;                 // 16-token sub-tiles per workgroup: BM =
 constexpr int kBM = 16 * kMT;
 constexpr int kXRows = 128;            // rows of an x buffer (all 128 loader lanes write; BM are read)
 constexpr int kXPitch = 144;           // 64 k (128 B) + 16 B pad
-constexpr int kWPitch = 80;            // 32 k (64 B) + 16 B pad
+constexpr int kWRow = 64;              // 32 k per row of a W buffer, no padding (pieces permuted instead)
 constexpr int kXBuf = kXRows * kXPitch; // 18432
 
 struct LinArgs {
@@ -78,10 +79,17 @@ __device__ __forceinline__ uint64_t uniform_u64(uint64_t v)
     return ((uint64_t)hi << 32) | lo;
 }
 
+// 16 bytes from "wave-uniform base + 32-bit lane offset" (the form the memory instructions take a
+// scalar base register pair for)
 __device__ __forceinline__ u32x4 gload16(uint64_t uniform_base, uint32_t lane_off)
 {
-    return *(const __attribute__((address_space(1))) u32x4 *)((gcptr_t)uniform_u64(uniform_base) + lane_off);
+    return *(const __attribute__((address_space(1))) u32x4 *)((gcptr_t)uniform_base + lane_off);
 }
+
+// Marks a lane value as redefined here (no instruction): its zero-extension to 64 bits then stays
+// next to the access that uses it, where "scalar base + 32-bit lane offset" is recognised; hoisted
+// out of the loop it would turn every access into a 64-bit vector addition.
+__device__ __forceinline__ void keep_in_loop(uint32_t &v) { asm volatile("" : "+v"(v)); }
 
 __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr)
 {
@@ -102,6 +110,76 @@ template <int M, int N> __device__ __forceinline__ uint32_t rational_pair(uint32
     y[0] = fwd_elem<false, M, N>(lo, c);
     y[1] = fwd_elem<false, M, N>(hi, c);
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(y, bf16x2));
+}
+
+// One matrix instruction, D = A B + D with D a 16 x 16 float32 tile (4 registers per lane), A the
+// weights (16 channels x 32 k), B the token operand (32 k x 16 tokens).  Written as inline assembly
+// so that the accumulators are pinned to the accumulation registers (AGPR = true) or to ordinary
+// vector registers (the tiles that do not fit the 256 accumulation registers): left to the register
+// allocator, a kernel that needs more than 256 registers shuffles hundreds of values between the
+// two files per stage.
+template <bool AGPR> __device__ __forceinline__ void mfma_16x16x32(f32x4 &acc, const bf16x8 &a, const bf16x8 &b)
+{
+    if constexpr (AGPR)
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    else
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
+// Nothing may be moved across this point by the instruction scheduler.
+__device__ __forceinline__ void fence_schedule() { __builtin_amdgcn_sched_barrier(0); }
+
+template <int I, int N, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// F of the two bfloat16 of one word, cut into seven pieces of about four vector instructions, one
+// to follow each matrix instruction of a 7-tile step: the matrix core works for 16 cycles per
+// instruction, in whose shadow the same wavefront can issue three to four other instructions.
+struct PairState {
+    float x0, x1, p0, p1, h0, h1;
+};
+
+template <int S> __device__ __forceinline__ void rational_piece(PairState &t, uint32_t w, const Coef<5, 4> &c, uint32_t &out)
+{
+    if constexpr (S == 0) {
+        t.x0 = __builtin_bit_cast(float, w << 16);
+        t.x1 = __builtin_bit_cast(float, w & 0xffff0000u);
+        t.p0 = fmaf(c.a[5], t.x0, c.a[4]);
+        t.p1 = fmaf(c.a[5], t.x1, c.a[4]);
+    } else if constexpr (S == 1) {
+        t.p0 = fmaf(t.p0, t.x0, c.a[3]);
+        t.p1 = fmaf(t.p1, t.x1, c.a[3]);
+        t.h0 = fmaf(c.b[3], t.x0, c.b[2]);
+        t.h1 = fmaf(c.b[3], t.x1, c.b[2]);
+    } else if constexpr (S == 2) {
+        t.p0 = fmaf(t.p0, t.x0, c.a[2]);
+        t.p1 = fmaf(t.p1, t.x1, c.a[2]);
+        t.h0 = fmaf(t.h0, t.x0, c.b[1]);
+        t.h1 = fmaf(t.h1, t.x1, c.b[1]);
+    } else if constexpr (S == 3) {
+        t.p0 = fmaf(t.p0, t.x0, c.a[1]);
+        t.p1 = fmaf(t.p1, t.x1, c.a[1]);
+        t.h0 = fmaf(t.h0, t.x0, c.b[0]);
+        t.h1 = fmaf(t.h1, t.x1, c.b[0]);
+    } else if constexpr (S == 4) {
+        t.p0 = fmaf(t.p0, t.x0, c.a[0]);
+        t.p1 = fmaf(t.p1, t.x1, c.a[0]);
+        t.h0 = t.h0 * t.x0;
+        t.h1 = t.h1 * t.x1;
+    } else if constexpr (S == 5) {
+        t.h0 = __builtin_amdgcn_rcpf(1.0f + fabsf(t.h0));
+        t.h1 = __builtin_amdgcn_rcpf(1.0f + fabsf(t.h1));
+    } else {
+        f32x2 y;
+        y[0] = t.p0 * t.h0;
+        y[1] = t.p1 * t.h1;
+        out = __builtin_bit_cast(uint32_t, __builtin_convertvector(y, bf16x2));
+    }
 }
 
 template <typename OUT> struct OutPack;
@@ -134,13 +212,16 @@ template <> struct OutPack<bf16_out> {
 template <int NT, typename OUT, bool NEDGE, int M, int N>
 __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const LinArgs a)
 {
+    static_assert(M == 5 && N == 4 && kMT == 7, "rational_piece is written for degrees (5, 4) and 7-tile steps");
     constexpr int MT = kMT;
+    constexpr int kAgprTiles = 64; // 256 accumulation registers hold 64 tiles; the rest live in vector registers
     constexpr int WN = 16 * NT;
     constexpr int BN = 4 * WN;
-    constexpr int kWBuf = BN * kWPitch;
+    constexpr int kWBuf = BN * kWRow;
     constexpr uint32_t kWs0 = 2 * kXBuf;
     extern __shared__ __align__(16) char smem[];
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+    const lptr_t lds = (lptr_t)smem;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -158,45 +239,65 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
     const int32_t n0 = nb * BN;
     const uint32_t K2 = (uint32_t)a.K * 2u; // bytes per row of x and W
 
-    // ---- x loader: waves 0, 1 take the first 32 k of a pair for rows 0..127, waves 2, 3 the last 32
+    // ---- x loader: waves 0, 1 take the first 32 k (64 bytes) of a pair, waves 2, 3 the last 32; a
+    // wave covers 64 rows with four loads of 16 rows each, four lanes per row, so that a load touches
+    // sixteen 64-byte segments (with one lane per row it would touch 64 and keep the address path of
+    // the vector cache busy four times as long).  Piece u of the lane's registers: row
+    // 64 (wave % 2) + 16 u + lane / 4, bytes 16 (lane % 4) .. of that row's 64.
     const int xhalf = wave >> 1;
-    const int xrow = (wave & 1) * 64 + lane;
-    int64_t xg = m0 + xrow;
-    if (xg > a.rows - 1)
-        xg = a.rows - 1; // rows past the end read the last row (never stored)
+    const int xrow0 = (wave & 1) * 64 + (lane >> 2);
     const uint64_t x_base = reinterpret_cast<uint64_t>(a.x) + (uint64_t)m0 * K2 + (uint64_t)xhalf * 64u;
-    const uint32_t x_lane = (uint32_t)((xg - m0) * (int64_t)K2);
-    uint32_t x_dst = lds0 + (uint32_t)xrow * kXPitch + (uint32_t)xhalf * 64u; // + buffer
+    uint32_t x_lane[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        int64_t xg = m0 + xrow0 + 16 * u;
+        if (xg > a.rows - 1)
+            xg = a.rows - 1; // rows past the end read the last row (never stored)
+        x_lane[u] = (uint32_t)((xg - m0) * (int64_t)K2) + (uint32_t)(lane & 3) * 16u;
+    }
+    // + buffer + 16 u rows
+    const uint32_t x_dst = lds0 + (uint32_t)xrow0 * kXPitch + (uint32_t)xhalf * 64u + (uint32_t)(lane & 3) * 16u;
+    constexpr uint32_t kXPieceStep = 16u * kXPitch;
 
-    // ---- W loader: unit i * 256 + tid -> row i * 64 + tid / 4, 16-byte piece tid % 4
-    const int wrow = tid >> 2;
-    const int wkg = tid & 3;
+    // ---- W loader: LDS-direct loads.  One wave instruction brings 16 rows x 64 bytes (32 k) and
+    // lands them in LDS as 1024 contiguous bytes, lane l at byte 16 l: row l / 4 of the 16, slot
+    // l % 4 of the row.  Instruction i of wave w covers rows 64 i + 16 w + 0..15 of the channel
+    // block.  Which 16-byte piece of its row a lane fetches is permuted (slot = piece xor g(row)) so
+    // that the operand reads below, 16 rows at one piece index, fall into 16 different 16-byte bank
+    // groups although rows are 64 bytes apart; g depends on the low four row bits only, i.e. on
+    // the lane.
+    const uint32_t w_g = (uint32_t)((lane >> 4) ^ (lane >> 3)) & 3u;
     const uint64_t w_base = reinterpret_cast<uint64_t>(a.W) + (uint64_t)n0 * K2;
     uint32_t w_lane[NEDGE ? NT : 1];
     if constexpr (NEDGE) {
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            int r = i * 64 + wrow;
+            int r = 64 * i + 16 * wave + (lane >> 2);
             if (n0 + r > a.Nout - 1)
                 r = a.Nout - 1 - n0;
-            w_lane[i] = (uint32_t)r * K2 + (uint32_t)wkg * 16u;
+            w_lane[i] = (uint32_t)r * K2 + (((uint32_t)lane & 3u) ^ w_g) * 16u;
         }
     } else {
-        w_lane[0] = (uint32_t)wrow * K2 + (uint32_t)wkg * 16u;
+        w_lane[0] = (uint32_t)(16 * wave + (lane >> 2)) * K2 + (((uint32_t)lane & 3u) ^ w_g) * 16u;
     }
-    const uint32_t w_dst = lds0 + kWs0 + (uint32_t)wrow * kWPitch + (uint32_t)wkg * 16u; // + buffer + i * 64 rows
-
-    auto w_load = [&](int i, uint32_t kbyte) -> u32x4 {
+    // stage at byte offset kbyte of the rows -> W buffer `buf`
+    auto w_fetch = [&](int i, uint32_t kbyte, int buf) {
+        const lptr_t dst = lds + kWs0 + (uint32_t)buf * kWBuf + (uint32_t)(4 * i + wave) * 1024u;
+        gcptr_t src;
         if constexpr (NEDGE)
-            return gload16(w_base + kbyte, w_lane[i]);
+            src = (gcptr_t)(w_base + kbyte) + w_lane[i];
         else
-            return gload16(w_base + kbyte + (uint64_t)i * 64u * K2, w_lane[0]);
+            src = (gcptr_t)(w_base + kbyte + (uint64_t)i * 64u * K2) + w_lane[0];
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                         (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
 
     // ---- operand reads: lane -> row lane % 16 of a 16-row sub-tile, 16-byte piece lane / 16
     const uint32_t xf_base = lds0 + (uint32_t)(lane & 15) * kXPitch + (uint32_t)(lane >> 4) * 16u;
+    // row r = wave WN + nt 16 + lane % 16: g(r) = ((r >> 2) ^ (r >> 1)) & 3 with r mod 16 = lane % 16
+    const uint32_t wf_g = (uint32_t)(((lane & 15) >> 2) ^ ((lane & 15) >> 1)) & 3u;
     const uint32_t wf_base =
-        lds0 + kWs0 + (uint32_t)(wave * WN + (lane & 15)) * kWPitch + (uint32_t)(lane >> 4) * 16u;
+        lds0 + kWs0 + (uint32_t)(wave * WN + (lane & 15)) * kWRow + (((uint32_t)(lane >> 4)) ^ wf_g) * 16u;
 
     f32x4 acc[NT][MT];
 #pragma unroll
@@ -205,112 +306,169 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
         for (int mt = 0; mt < MT; ++mt)
             acc[nt][mt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
+    // The contraction runs over pairs of stages (64 k = 128 bytes of a row) in rotated order: this
+    // workgroup starts at pair `rot` and wraps around.  Rows of x and W are K2 bytes apart, which for
+    // the model shapes is a multiple of 16 cache lines, so the same 128 bytes of every row sit in one
+    // L2 channel; workgroups that all walk K from 0 would hammer one channel at a time.  With the
+    // workgroups of an XCD started at different pairs their fetches spread over all channels.  The
+    // order of summation of an output stays fixed by the shape (it is the rotation of its token block).
     const int32_t n_pairs = a.K >> 6;
-    const uint32_t k_last_stage = K2 - 64u;  // byte offset of the last 32-k stage in a row
-    const uint32_t k_last_pair = K2 - 128u;
+    const uint32_t rot = ((uint32_t)mb >> 3) % (uint32_t)n_pairs;
+    auto next_pair = [&](uint32_t pp) { return pp + 1u == (uint32_t)n_pairs ? 0u : pp + 1u; };
 
-    // coefficients of the group the wave's next F work lies in
-    int g_cur = (xhalf * 32) / a.dgc;
-    Coef<M, N> c = load_coef<M, N>(a.A, a.B, g_cur);
+    // Coefficients of the group the wave's next F work lies in: wave-uniform, in scalar registers,
+    // reloaded once per pair.  Explicit scalar loads: inside the loop the compiler cannot show that
+    // nothing has written A and B since the kernel started and would fetch them through the vector
+    // memory path, into vector registers, with a wait on the vector-memory counter (and so on the
+    // x and W loads just issued) in front of the first use.  (A quotient of an integer division is
+    // formed by vector instructions, hence the readfirstlane.)
+    Coef<M, N> c;
     auto coef_for = [&](uint32_t kbyte_pair) {
-        const int g = (int)((kbyte_pair / 2u + (uint32_t)xhalf * 32u) / (uint32_t)a.dgc);
-        if (g != g_cur) {
-            g_cur = g;
-            c = load_coef<M, N>(a.A, a.B, g);
-        }
-    };
-
-    u32x4 xq[4];  // this lane's 32 k of the pair F works on next
-    u32x4 wr[NT]; // this lane's pieces of the next W stage
-
-    // ---- prologue: pair 0 and stage 0 into LDS, pair 1 and stage 1 into registers
+        const int g = __builtin_amdgcn_readfirstlane((int)((kbyte_pair / 2u + (uint32_t)xhalf * 32u) / (uint32_t)a.dgc));
+        const float *pa = a.A + (size_t)g * (M + 1);
+        const float *pb = a.B + (size_t)g * N;
+        f32x4 a03, b14;
+        f32x2 a45;
+        asm volatile("s_load_dwordx4 %0, %3, 0x0\n\t"
+                     "s_load_dwordx2 %1, %3, 0x10\n\t"
+                     "s_load_dwordx4 %2, %4, 0x0\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&s"(a03), "=&s"(a45), "=&s"(b14)
+                     : "s"(pa), "s"(pb)
+                     : "memory");
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
-        xq[u] = gload16(x_base, x_lane + (uint32_t)u * 16u);
+        for (int i = 0; i < 4; ++i) {
+            c.a[i] = a03[i];
+            c.b[i] = b14[i];
+        }
+        c.a[4] = a45[0];
+        c.a[5] = a45[1];
+    };
+    uint32_t pp = rot; // the pair the matrix products work on
+    coef_for(pp * 128u);
+
+    u32x4 xq[4]; // this lane's four 16-byte pieces (8 k each, of four rows) of the pair F works on next
+
+    // ---- prologue: the first stage of W and F(first pair) into LDS, the first half of the second pair into registers
 #pragma unroll
     for (int i = 0; i < NT; ++i)
-        wr[i] = w_load(i, 0);
+        w_fetch(i, pp * 128u, 0);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        xq[u] = gload16(x_base + pp * 128u, x_lane[u]);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         u32x4 y;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             y[j] = rational_pair<M, N>(xq[u][j], c);
-        lds_write16(x_dst + (uint32_t)u * 16u, y);
+        lds_write16(x_dst + (uint32_t)u * kXPieceStep, y);
     }
-#pragma unroll
-    for (int i = 0; i < NT; ++i)
-        lds_write16(w_dst + (uint32_t)i * 64u * kWPitch, wr[i]);
     {
-        const uint32_t kp = n_pairs > 1 ? 128u : k_last_pair;
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            xq[u] = gload16(x_base + kp, x_lane + (uint32_t)u * 16u);
+        const uint32_t kp = next_pair(pp) * 128u;
+        xq[0] = gload16(x_base + kp, x_lane[0]);
+        xq[1] = gload16(x_base + kp, x_lane[1]);
         coef_for(kp);
-#pragma unroll
-        for (int i = 0; i < NT; ++i)
-            wr[i] = w_load(i, 64u);
     }
     __syncthreads();
 
-    // One stage: the matrix products of stage s = 2 p + Q from LDS, and beside them the
-    // hand-over of stage s + 1 (registers -> LDS; its successor s + 2 -> registers) and half of
-    // F for pair p + 1.  Addresses past the end of K are clamped to the last stage / pair: the
-    // surplus loads read valid memory and what they bring is never consumed.
-    auto stage = [&](auto Qc, uint32_t xsel_read, uint32_t xsel_write, uint32_t kbyte_stage2, uint32_t kbyte_pair2) {
+    // One stage: the matrix products of stage s = 2 p + Q from LDS.  Beside them: the next stage of
+    // W goes from memory straight into the other W buffer; one half of the x registers is refilled
+    // (the half that was consumed one stage ago); F is evaluated on the other half, which holds
+    // 16 k of pair p + 1, and written to the other x buffer.  Everything that is in flight has
+    // arrived when the stage ends (the barrier waits for the LDS-direct loads and, the load counter
+    // being in order, for all loads).  The loads issued during the last pair (for pairs that would
+    // come after it) wrap around to valid memory; what they bring is never consumed.
+    // The order of the instructions is the one written here: every matrix instruction is followed
+    // by a piece of F and a scheduling fence (see rational_piece).
+    auto stage = [&](auto Qc, uint32_t xsel_read, uint32_t xsel_write, uint32_t kbyte_next_stage,
+                     uint32_t kbyte_refill) {
         constexpr int Q = decltype(Qc)::value;
+        constexpr int kPairsPerStep = (8 + NT - 1) / NT;
         const uint32_t xb = xf_base + xsel_read + (uint32_t)Q * 64u;
         const uint32_t wb = wf_base + (uint32_t)Q * kWBuf;
-        const uint32_t wd = w_dst + (uint32_t)(1 - Q) * kWBuf;
         bf16x8 xf[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
             xf[mt] = lds_read16(xb + (uint32_t)mt * 16u * kXPitch);
-        bf16x8 wf = lds_read16(wb);
-        u32x4 y0, y1;
+        // weight operands two steps ahead of their use (an LDS read takes longer than the 7 matrix
+        // instructions of one step)
+        bf16x8 wf[3];
+        wf[0] = lds_read16(wb);
+        if constexpr (NT > 1)
+            wf[1] = lds_read16(wb + 16u * kWRow);
+        // refill pieces 2 (1 - Q), 2 (1 - Q) + 1 of the x registers
+        keep_in_loop(x_lane[2 * (1 - Q)]);
+        keep_in_loop(x_lane[2 * (1 - Q) + 1]);
+        xq[2 * (1 - Q)] = gload16(x_base + kbyte_refill, x_lane[2 * (1 - Q)]);
+        xq[2 * (1 - Q) + 1] = gload16(x_base + kbyte_refill, x_lane[2 * (1 - Q) + 1]);
+        if constexpr (NEDGE) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            bf16x8 wf_next = wf;
-            if (nt + 1 < NT)
-                wf_next = lds_read16(wb + (uint32_t)(nt + 1) * 16u * kWPitch);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf[mt], acc[nt][mt], 0, 0, 0);
-            // stage s + 1 of W: registers -> LDS, then stage s + 2 -> registers
-            lds_write16(wd + (uint32_t)nt * 64u * kWPitch, wr[nt]);
-            wr[nt] = w_load(nt, kbyte_stage2);
-            // F on this stage's share of pair p + 1: words 8 Q' .. of the lane's 16 words
-#pragma unroll
-            for (int j = nt; j < 8; j += NT) {
-                const uint32_t r = rational_pair<M, N>(xq[2 * Q + (j >> 2)][j & 3], c);
-                if (j < 4)
-                    y0[j] = r;
-                else
-                    y1[j - 4] = r;
-            }
-            wf = wf_next;
+            for (int i = 0; i < NT; ++i)
+                keep_in_loop(w_lane[i]);
+        } else {
+            keep_in_loop(w_lane[0]);
         }
-        lds_write16(x_dst + xsel_write + (uint32_t)(2 * Q) * 16u, y0);
-        lds_write16(x_dst + xsel_write + (uint32_t)(2 * Q + 1) * 16u, y1);
-        xq[2 * Q] = gload16(x_base + kbyte_pair2, x_lane + (uint32_t)(2 * Q) * 16u);
-        xq[2 * Q + 1] = gload16(x_base + kbyte_pair2, x_lane + (uint32_t)(2 * Q + 1) * 16u);
+        u32x4 y0, y1;
+        fence_schedule();
+        static_for<0, NT>([&](auto ntc) {
+            constexpr int nt = decltype(ntc)::value;
+            // the next stage of W, two fetches per step, so that the last is issued before half of
+            // this stage is over and has the rest of it to arrive (all of them at once at the start
+            // of the stage was measured 10 % slower: the wave then waits at the memory instructions
+            // before its first matrix instruction)
+            if constexpr (2 * nt < NT)
+                w_fetch(2 * nt, kbyte_next_stage, 1 - Q);
+            if constexpr (2 * nt + 1 < NT)
+                w_fetch(2 * nt + 1, kbyte_next_stage, 1 - Q);
+            if constexpr (nt + 2 < NT)
+                wf[(nt + 2) % 3] = lds_read16(wb + (uint32_t)(nt + 2) * 16u * kWRow);
+            fence_schedule();
+            PairState ps[kPairsPerStep];
+            uint32_t res[kPairsPerStep];
+            static_for<0, MT>([&](auto mtc) {
+                constexpr int mt = decltype(mtc)::value;
+                mfma_16x16x32<(nt * MT + mt) < kAgprTiles>(acc[nt][mt], wf[nt % 3], xf[mt]);
+                // F on this step's share: words nt, nt + NT, .. of the lane's 8 words of this stage
+                static_for<0, kPairsPerStep>([&](auto ic) {
+                    constexpr int j = nt + decltype(ic)::value * NT;
+                    if constexpr (j < 8)
+                        rational_piece<mt>(ps[decltype(ic)::value], xq[2 * Q + (j >> 2)][j & 3], c, res[decltype(ic)::value]);
+                });
+                fence_schedule();
+            });
+            static_for<0, kPairsPerStep>([&](auto ic) {
+                constexpr int j = nt + decltype(ic)::value * NT;
+                if constexpr (j < 4)
+                    y0[j] = res[decltype(ic)::value];
+                else if constexpr (j < 8)
+                    y1[j - 4] = res[decltype(ic)::value];
+            });
+        });
+        lds_write16(x_dst + xsel_write + (uint32_t)(2 * Q) * kXPieceStep, y0);
+        lds_write16(x_dst + xsel_write + (uint32_t)(2 * Q + 1) * kXPieceStep, y1);
         __syncthreads();
     };
 
     uint32_t xsel = 0; // buffer the matrix products read
     for (int32_t p = 0; p < n_pairs; ++p) {
-        const uint32_t s2 = (uint32_t)(2 * p + 2) * 64u; // byte offset of stage 2 p + 2
-        const uint32_t s3 = s2 + 64u;
-        const uint32_t p2 = (uint32_t)(p + 2) * 128u;
-        const uint32_t kb2 = s2 < k_last_stage ? s2 : k_last_stage;
-        const uint32_t kb3 = s3 < k_last_stage ? s3 : k_last_stage;
-        const uint32_t kp2 = p2 < k_last_pair ? p2 : k_last_pair;
-        stage(std::integral_constant<int, 0>{}, xsel, kXBuf - xsel, kb2, kp2);
-        stage(std::integral_constant<int, 1>{}, xsel, kXBuf - xsel, kb3, kp2);
-        // F of pair p + 2 (computed during pair p + 1) uses the group of that pair
-        coef_for(kp2);
+        const uint32_t p1 = next_pair(pp);
+        const uint32_t p2 = next_pair(p1);
+        // first stage of the pair: fetch its second stage of W; refill pieces 2, 3 with the next pair;
+        // F on pieces 0, 1 of the next pair
+        stage(std::integral_constant<int, 0>{}, xsel, kXBuf - xsel, pp * 128u + 64u, p1 * 128u);
+        // second stage: fetch the first stage of the next pair; refill pieces 0, 1 with the pair after
+        // it; F on pieces 2, 3 of the next pair
+        stage(std::integral_constant<int, 1>{}, xsel, kXBuf - xsel, p1 * 128u, p2 * 128u);
+        // F during the next pair works on the pair after it
+        coef_for(p2 * 128u);
         xsel = kXBuf - xsel;
+        pp = p1;
     }
+
+    // the matrix instructions above are opaque to the compiler's hazard tracking: let the last of
+    // them drain before their results are read
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
     // ---- epilogue: lane holds channels n0 + wave WN + nt 16 + (lane / 16) 4 + 0..3 of token m0 + mt 16 + lane % 16
     const int32_t o_lane = n0 + wave * WN + (lane >> 4) * 4;
@@ -340,6 +498,7 @@ using LinKernel = void (*)(const LinArgs);
 template <typename OUT> static LinKernel select_kernel(int nt, bool nedge)
 {
     switch (nt) {
+    case 12: return grkan_linear_fwd_kernel<12, OUT, false, 5, 4>;
     case 6: return grkan_linear_fwd_kernel<6, OUT, false, 5, 4>;
     case 3:
         return nedge ? grkan_linear_fwd_kernel<3, OUT, true, 5, 4> : grkan_linear_fwd_kernel<3, OUT, false, 5, 4>;
@@ -347,7 +506,7 @@ template <typename OUT> static LinKernel select_kernel(int nt, bool nedge)
     return nullptr;
 }
 
-static size_t lds_bytes(int nt) { return (size_t)2 * kXBuf + (size_t)2 * (64 * nt) * kWPitch; }
+static size_t lds_bytes(int nt) { return (size_t)2 * kXBuf + (size_t)2 * (64 * nt) * kWRow; }
 
 // The kernels use more LDS than the default limit for dynamic shared memory; raise it once per
 // kernel and device.
@@ -406,7 +565,7 @@ extern "C" grkan_status_t grkan_linear_fwd(const void *x, const float *A, const 
     if (rows == 0)
         return GRKAN_OK;
 
-    const int nt = D_out % 384 == 0 ? 6 : 3;
+    const int nt = D_out % 768 == 0 ? 12 : (D_out % 384 == 0 ? 6 : 3);
     const int bn = 64 * nt;
     const bool nedge = D_out % bn != 0;
     const LinKernel kernel = out_dtype == GRKAN_BF16 ? select_kernel<bf16_out>(nt, nedge) : select_kernel<float>(nt, nedge);
