@@ -89,6 +89,12 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the HIP-graph leg (one rotation of steps captured once and replayed: what a "
                          "launch-bound caller gains; the entry points only enqueue kernels)")
+    ap.add_argument("--fused-linear", action="store_true",
+                    help="measure only the fused GR-KAN layer forward out = W F(x) + bias (grkan_linear_fwd, bfloat16, "
+                         "one MFMA kernel) at the workload's two layer shapes against grkan_fwd followed by torch's "
+                         "matrix product, and print its own JSON line (roofline: dense bf16 MFMA peak)")
+    ap.add_argument("--no-fused", action="store_true",
+                    help="skip the short fused-layer measurement that is part of the default line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of x2's size (for scaling profiler byte counters)")
     return ap.parse_args()
@@ -222,6 +228,84 @@ def cpu_baseline(cases):
     }
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bfloat16 matrix peak, published
+
+
+def fused_linear_bench(torch, grkan, grkan_inputs, workload, launches, layers_wanted=("x2", "x1"), copy_calibration=False):
+    """The fused layer forward at the workload's layer shapes (x1 -> 4 D, x2 -> D / 4), bfloat16:
+    grkan_linear_fwd against grkan_fwd + torch.addmm (the library matrix product) and the matrix
+    product alone, each the mean of `launches` event-timed launches rotating over four input sets
+    (the inputs of the wide layer are 155 MB each: no launch finds its x in the last-level cache)."""
+    out = {}
+    cfg = grkan_inputs.CONFIGS[workload]
+    names = [t for t, _ in cfg.tensors]
+    for tensor in layers_wanted:
+        if tensor not in names:
+            continue
+        case = grkan_inputs.make_linear_case(workload, tensor)
+        dev = grkan_inputs.upload_linear(case)
+        rows, K, N = case["rows"], case["D_in"], case["D_out"]
+        sets = 4
+        xs = [dev["x"]] + [dev["x"].clone() for _ in range(sets - 1)]
+        outs = [torch.empty(rows, N, device="cuda:0", dtype=torch.bfloat16) for _ in range(sets)]
+        ys = [torch.empty_like(dev["x"]) for _ in range(sets)]
+        bias16 = dev["bias"].to(torch.bfloat16)
+        Wt = dev["W"].t()
+        flop = 2.0 * rows * K * N
+
+        def fused(i):
+            grkan.grkan_linear_fwd(xs[i % sets], dev["A"], dev["B"], dev["W"], dev["bias"], out=outs[i % sets])
+
+        def two_kernels(i):
+            grkan.grkan_fwd(xs[i % sets], dev["A"], dev["B"], out=ys[i % sets])
+            torch.addmm(bias16, ys[i % sets], Wt, out=outs[i % sets])
+
+        def product_only(i):
+            torch.addmm(bias16, ys[i % sets], Wt, out=outs[i % sets])
+
+        res = {"shape": "[%d,%d] x [%d,%d]^T" % (rows, K, N, K), "GFLOP": flop / 1e9}
+        for key, fn in (("fused", fused), ("grkan_fwd_plus_library_matmul", two_kernels), ("library_matmul_alone", product_only)):
+            for i in range(5):
+                fn(i)
+            mean, med, mn, ci = launch_stats(torch, fn, launches)
+            res[key] = {"avg_us": mean * 1e3, "ci95_us": ci * 1e3, "median_us": med * 1e3, "min_us": mn * 1e3,
+                        "TFLOP/s": flop / (mean * 1e-3) / 1e12}
+        res["fused_over_two_kernels"] = res["fused"]["avg_us"] / res["grkan_fwd_plus_library_matmul"]["avg_us"]
+        # bytes the method has to move: x and W read once, out written once
+        res["algorithmic_bytes"] = 2 * (rows * K + N * K + rows * N) + 4 * N
+        if copy_calibration:
+            for i in range(3):
+                ys[i % sets].copy_(xs[i % sets])
+            torch.cuda.synchronize()
+        out["fc2" if tensor == "x2" else "fc1"] = res
+        del xs, outs, ys, dev
+        torch.cuda.empty_cache()
+    return out
+
+
+def fused_linear_main(args, torch, grkan, grkan_inputs):
+    res = fused_linear_bench(torch, grkan, grkan_inputs, args.workload, max(20, args.steps),
+                             copy_calibration=args.copy_calibration)
+    dom = res.get("fc2") or next(iter(res.values()))
+    achieved = dom["fused"]["TFLOP/s"]
+    traffic, traffic_src = measured_traffic("%s/bf16/linear_fwd_fc2" % args.workload)
+    line = {
+        "metric": "fused GR-KAN layer forward out = W F(x) + bias, %s shapes: time and fraction of the MFMA peak"
+                  % WORKLOAD_LABEL[args.workload],
+        "value": achieved, "unit": "TFLOP/s", "n_gpus": 1, "steps": max(20, args.steps), "warmup": 5,
+        "ms_per_step": dom["fused"]["avg_us"] / 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (args.workload, "; ".join("%s %s" % (k, v["shape"]) for k, v in res.items()))},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
+                     "kernel": "grkan_linear_fwd_kernel on %s, %.1f GFLOP per launch, avg %.2f us"
+                               % (dom["shape"], dom["GFLOP"], dom["fused"]["avg_us"])},
+        "detail": res,
+        "device": device_report(torch, grkan),
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -239,6 +323,9 @@ def main():
         sys.exit(2)
     grkan.load_library()  # raises if the HIP library is not built: there is no fallback
     torch.cuda.set_device(0)
+    if args.fused_linear:
+        fused_linear_main(args, torch, grkan, grkan_inputs)
+        return
 
     cfg = grkan_inputs.CONFIGS[args.workload]
     G = args.groups if args.groups > 0 else cfg.G
@@ -469,8 +556,17 @@ def main():
         out["alg1_baseline"] = alg1
     if block is not None:
         out["mlp_block"] = block
+    if not args.no_fused and args.workload in ("kat_t", "kat_s", "kat_b") and (m_deg, n_deg) == (5, 4):
+        # the layer one level up (Eq. "GR_KAN"): F fused into the matrix product that consumes it; the wide layer only
+        try:
+            del layers, dom
+            torch.cuda.empty_cache()
+            out["fused_layer_forward"] = fused_linear_bench(torch, grkan, grkan_inputs, args.workload, 20, ("x2",))
+        except grkan.GrkanError as exc:
+            out["fused_layer_forward"] = {"error": str(exc)}
+        layers = dom = None
     if not args.no_cpu_baseline:
-        del layers, dom
+        layers = dom = None
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(cases)
     print(json.dumps(out))

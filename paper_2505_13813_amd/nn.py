@@ -2,8 +2,9 @@
 kernels, the group-wise rational module with the paper's model-level
 conventions, the GR-KAN linear layer and the KAT MLP block.
 
-Only the rational function runs in this package's kernels; the matrix products
-are torch's (library GEMMs).  Conventions taken from the FlashKAT paper:
+The rational function runs in this package's kernels; the matrix products are
+torch's (library GEMMs), except where the one-kernel layer grkan_linear_fwd is
+selected (GRKANLinear(fused=...)).  Conventions taken from the FlashKAT paper:
   * GR-KAN(x) = W F(x): the rational function is applied to the INPUT of each
     linear layer (Eq. "GR_KAN").
   * the groups use one common set of numerator coefficients and have their own
@@ -69,6 +70,47 @@ class GroupRationalFunction(torch.autograd.Function):
         ws = _workspace(x, int(x.numel() // D) if D else 0, D, int(A.shape[0]))
         dx, dA, dB = binding.grkan_bwd(x, dy.contiguous(), A, B, workspace=ws)
         return dx, dA, dB
+
+
+def fused_layer_supported(x, A, weight) -> bool:
+    """Shapes and types the one-kernel layer (grkan_linear_fwd) covers: bfloat16 x and W on the GPU,
+    degrees (5, 4), D_in a multiple of 64, d_g a multiple of 32, D_out a multiple of 4."""
+    D_in, G = int(x.shape[-1]), int(A.shape[0])
+    return (x.is_cuda and x.dtype == torch.bfloat16 and weight.dtype == torch.bfloat16 and int(A.shape[1]) == 6
+            and D_in % 64 == 0 and D_in % G == 0 and (D_in // G) % 32 == 0 and int(weight.shape[0]) % 4 == 0)
+
+
+class GRKANLayerFunction(torch.autograd.Function):
+    """out = F(x) W^T + bias with the forward pass in one kernel (F never written to memory) and
+    nothing but x, A, B, W saved.  The backward pass recomputes F(x) for dW = dOut^T F(x)
+    (grkan_fwd + a library product), forms dF = dOut W (library product) and runs grkan_bwd on it:
+    one extra elementwise forward kernel in exchange for not keeping F(x) alive between the passes."""
+
+    @staticmethod
+    def forward(ctx, x, A, B, weight, bias):
+        x = x.contiguous()
+        A = A.contiguous()
+        B = B.contiguous()
+        weight = weight.contiguous()
+        ctx.save_for_backward(x, A, B, weight)
+        ctx.has_bias = bias is not None
+        ctx.bias_dtype = bias.dtype if bias is not None else None
+        b32 = bias.to(torch.float32).contiguous() if bias is not None else None
+        return binding.grkan_linear_fwd(x, A, B, weight, b32, out_dtype=x.dtype)
+
+    @staticmethod
+    def backward(ctx, dout):
+        x, A, B, weight = ctx.saved_tensors
+        D_in, D_out = int(x.shape[-1]), int(weight.shape[0])
+        dout2 = dout.contiguous().view(-1, D_out)
+        y = binding.grkan_fwd(x, A, B).view(-1, D_in)      # F(x), recomputed
+        dW = dout2.t().mm(y)
+        dF = dout2.mm(weight).view(x.shape)
+        rows = int(x.numel() // D_in) if D_in else 0
+        ws = _workspace(x, rows, D_in, int(A.shape[0]))
+        dx, dA, dB = binding.grkan_bwd(x, dF, A, B, workspace=ws)
+        dbias = dout2.sum(0).to(ctx.bias_dtype) if ctx.has_bias else None
+        return dx, dA, dB, dW, dbias
 
 
 def group_rational(x, A, B):
@@ -158,10 +200,16 @@ class GRKANLinear(nn.Module):
 
     def __init__(self, in_features: int, out_features: int, groups: int = 8, init: str = "identity",
                  bias: bool = True, shared_numerator: bool = True,
-                 degrees: Tuple[int, int] = (M_DEGREE, N_DEGREE)):
+                 degrees: Tuple[int, int] = (M_DEGREE, N_DEGREE), fused: str = "inference"):
+        """`fused`: when the one-kernel layer (F inside the matrix product) is used where it applies
+        (bfloat16, see fused_layer_supported): "inference" = only when no gradient is recorded (the
+        default: in training its backward pass has to recompute F(x)), "always", or "never"."""
         super().__init__()
         if in_features % groups:
             raise ValueError("in_features must be a multiple of groups")
+        if fused not in ("inference", "always", "never"):
+            raise ValueError("fused must be 'inference', 'always' or 'never'")
+        self.fused = fused
         self.rational = GroupRational(groups, init, shared_numerator, degrees)
         self.linear = nn.Linear(in_features, out_features, bias=bias)
         alpha = 1.0 / self.rational.second_moment()  # Var[x] / E[F(x)^2] with Var[x] = 1
@@ -171,6 +219,12 @@ class GRKANLinear(nn.Module):
                 self.linear.bias.zero_()
 
     def forward(self, x):
+        if self.fused != "never":
+            A, B = self.rational.coefficient_rows()
+            want = self.fused == "always" or not torch.is_grad_enabled()
+            if want and fused_layer_supported(x, A, self.linear.weight):
+                return GRKANLayerFunction.apply(x, A.to(torch.float32), B.to(torch.float32), self.linear.weight,
+                                                self.linear.bias)
         return self.linear(self.rational(x))
 
 
@@ -179,11 +233,13 @@ class KATMlp(nn.Module):
     the first rational starts as the identity, the second as Swish."""
 
     def __init__(self, dim: int, hidden: int | None = None, groups: int = 8,
-                 degrees: Tuple[int, int] = (M_DEGREE, N_DEGREE)):
+                 degrees: Tuple[int, int] = (M_DEGREE, N_DEGREE), fused: str = "inference"):
         super().__init__()
         hidden = 4 * dim if hidden is None else hidden
-        self.fc1 = GRKANLinear(dim, hidden, groups, init="identity", degrees=degrees)
-        self.fc2 = GRKANLinear(hidden, dim, groups, init="swish", degrees=degrees)
+        # the one-kernel layer pays for the wide input (fc2: long contraction, few outputs); for fc1
+        # the library product after the elementwise kernel is faster on this hardware
+        self.fc1 = GRKANLinear(dim, hidden, groups, init="identity", degrees=degrees, fused="never")
+        self.fc2 = GRKANLinear(hidden, dim, groups, init="swish", degrees=degrees, fused=fused)
 
     def forward(self, x):
         return self.fc2(self.fc1(x))

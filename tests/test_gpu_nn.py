@@ -103,3 +103,47 @@ def test_kat_mlp_block_forward_backward(oracle, degrees):
     close(mlp.fc1.rational.numerator.grad, dA1.sum(0), 2e-4)
     close(mlp.fc2.linear.weight.grad, g0.T @ f2, 2e-4)
     close(mlp.fc1.linear.weight.grad, dh.T @ f1, 2e-4)
+
+
+def test_fused_layer_module_forward_and_backward(oracle):
+    """GRKANLinear(fused="always"): the forward pass is the one-kernel layer, the backward pass
+    recomputes F(x); gradients against the oracle's chain rule (bfloat16 storage throughout, so the
+    comparison is coarse: it checks the wiring -- which product, which transpose, which sum)."""
+    import torch
+
+    import paper_2505_13813_amd as grkan
+    from paper_2505_13813_amd import nn as gnn
+
+    torch.manual_seed(1)
+    rows, D_in, D_out, G = 160, 256, 64, 8
+    layer = gnn.GRKANLinear(D_in, D_out, G, init="swish", fused="always").to("cuda:0").to(torch.bfloat16)
+    with torch.no_grad():
+        layer.rational.numerator.add_(torch.randn_like(layer.rational.numerator) * 0.05)
+        layer.rational.denominator.add_(torch.randn_like(layer.rational.denominator) * 0.05)
+        layer.linear.bias.normal_(0.0, 0.1)
+    x = torch.randn(rows, D_in, device="cuda:0").to(torch.bfloat16).requires_grad_(True)
+    dout = torch.randn(rows, D_out, device="cuda:0").to(torch.bfloat16)
+    A, B = layer.rational.coefficient_rows()
+    assert gnn.fused_layer_supported(x, A, layer.linear.weight)
+    out = layer(x)
+    direct = grkan.grkan_linear_fwd(x.detach(), A.float().contiguous(), B.float().contiguous(),
+                                    layer.linear.weight.detach(), layer.linear.bias.detach().float())
+    assert torch.equal(out.detach().view(torch.int16), direct.view(torch.int16))
+    out.backward(dout)
+    torch.cuda.synchronize()
+
+    f64 = lambda t: t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+    A64, B64 = f64(A.float()), f64(B.float())
+    ref = oracle.linear_bwd(f64(x), f64(dout), A64, B64, f64(layer.linear.weight))
+    close = lambda g, r, tol: np.max(np.abs(g - r)) <= tol * np.max(np.abs(r))
+    assert close(f64(x.grad), ref["dx"], 3e-2)
+    assert close(f64(layer.linear.weight.grad), ref["dW"], 3e-2)
+    assert close(f64(layer.linear.bias.grad), ref["dbias"], 3e-2)
+    assert close(f64(layer.rational.denominator.grad), ref["dB"], 5e-2)
+    # one shared numerator row: the sum of the per-group gradients
+    assert close(f64(layer.rational.numerator.grad), ref["dA"].sum(0), 5e-2)
+    # inference mode of the default setting takes the fused kernel, training the two-kernel path
+    auto = gnn.GRKANLinear(D_in, D_out, G, init="swish").to("cuda:0").to(torch.bfloat16)
+    auto.load_state_dict(layer.state_dict())
+    with torch.no_grad():
+        assert torch.equal(auto(x).view(torch.int16), direct.view(torch.int16))
