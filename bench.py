@@ -528,7 +528,7 @@ def main():
             block[dt_name] = res
 
     out = {
-        "metric": "GR-KAN fwd+bwd elements/s and achieved HBM GB/s (% of peak), %s shape"
+        "metric": "GR-KAN fwd+bwd elements/s and achieved HBM GB/s (%% of peak), %s shape"
                   % WORKLOAD_LABEL[args.workload],
         "value": elems_per_step / (dt / args.steps),
         "unit": "elements/s",

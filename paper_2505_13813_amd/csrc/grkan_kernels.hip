@@ -79,7 +79,7 @@ __device__ __forceinline__ float bwd_elem(float x, float d, const Coef<M, N> &c,
     const float sr = aden != 0.0f ? __builtin_copysignf(r, aden) : 0.0f;
     // acc[M+1..] collect +dy s P x^j / Q^2; the minus sign of Eq. "grad_b" is
     // applied once per lane after the loop (negate_b_sums)
-    const float wb = d * ((p * r) * sr); // dy s P / Q^2
+    const float wb = t * (p * sr); // (dy / Q) (P s / Q) = dy s P / Q^2
 #pragma unroll
     for (int j = 1; j <= N; ++j)
         acc[M + j] = fmaf(wb, pw[j], acc[M + j]);
