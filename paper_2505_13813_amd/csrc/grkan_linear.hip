@@ -49,7 +49,6 @@ typedef const __attribute__((address_space(1))) char *gcptr_t;
 typedef __attribute__((address_space(1))) char *gptr_t;
 typedef __attribute__((address_space(3))) char *lptr_t;
 
-constexpr int kThreads = 256;
 constexpr int kMT = 7;                 // 16-token sub-tiles per workgroup: BM = 112
 constexpr int kBM = 16 * kMT;
 constexpr int kXRows = 128;            // rows of an x buffer (all 128 loader lanes write; BM are read)
@@ -207,16 +206,24 @@ template <> struct OutPack<bf16_out> {
     }
 };
 
-// NT: 16-channel sub-tiles per wavefront (BN = 64 NT).  NEDGE: the last channel
+// NW: wavefronts per workgroup (4: one per SIMD; 8: two per SIMD, each with half the registers, so
+// that one wavefront's waits at memory instructions and barriers are covered by the other's matrix
+// instructions).  NT: 16-channel sub-tiles per wavefront (BN = 16 NW NT).  NEDGE: the last channel
 // block may be partial (weight rows are clamped, stores predicated).
-template <int NT, typename OUT, bool NEDGE, int M, int N>
-__global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const LinArgs a)
+template <int NW, int NT, typename OUT, bool NEDGE, int M, int N>
+__global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinArgs a)
 {
     static_assert(M == 5 && N == 4 && kMT == 7, "rational_piece is written for degrees (5, 4) and 7-tile steps");
+    static_assert(NW == 4 || NW == 8, "4 or 8 wavefronts");
     constexpr int MT = kMT;
-    constexpr int kAgprTiles = 64; // 256 accumulation registers hold 64 tiles; the rest live in vector registers
+    // Accumulator tiles pinned to accumulation registers; the rest live in vector registers.  One wave
+    // per SIMD has 256 of each kind; with two waves per SIMD the compiler splits a wave's 256
+    // registers evenly, 128 accumulation registers (32 tiles) and 128 vector registers.
+    constexpr int kAgprTiles = NW == 8 ? 32 : 64;
     constexpr int WN = 16 * NT;
-    constexpr int BN = 4 * WN;
+    constexpr int BN = NW * WN;
+    constexpr int U = 16 / NW;   // 16-byte pieces of x a lane holds per pair of stages
+    constexpr int PPS = U / 2;   // ... of which it works on per stage
     constexpr int kWBuf = BN * kWRow;
     constexpr uint32_t kWs0 = 2 * kXBuf;
     extern __shared__ __align__(16) char smem[];
@@ -239,17 +246,18 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
     const int32_t n0 = nb * BN;
     const uint32_t K2 = (uint32_t)a.K * 2u; // bytes per row of x and W
 
-    // ---- x loader: waves 0, 1 take the first 32 k (64 bytes) of a pair, waves 2, 3 the last 32; a
-    // wave covers 64 rows with four loads of 16 rows each, four lanes per row, so that a load touches
-    // sixteen 64-byte segments (with one lane per row it would touch 64 and keep the address path of
-    // the vector cache busy four times as long).  Piece u of the lane's registers: row
-    // 64 (wave % 2) + 16 u + lane / 4, bytes 16 (lane % 4) .. of that row's 64.
-    const int xhalf = wave >> 1;
-    const int xrow0 = (wave & 1) * 64 + (lane >> 2);
+    // ---- x loader.  A pair of stages needs 128 rows x 128 bytes of x: 16 units of (16 rows, one
+    // 64-byte half), one load instruction each, four lanes per row, so that a load touches sixteen
+    // 64-byte segments (with one lane per row it would touch 64 and keep the address path of the
+    // vector cache busy four times as long).  Wave w takes units U w .. U w + U - 1; unit q is half
+    // q / 8 (wave-uniform: one coefficient group per wave and pair), rows 16 (q % 8) + lane / 4,
+    // bytes 16 (lane % 4) .. of the half.
+    const int xhalf = (wave * U) >> 3;
+    const int xrow0 = ((wave * U) & 7) * 16 + (lane >> 2);
     const uint64_t x_base = reinterpret_cast<uint64_t>(a.x) + (uint64_t)m0 * K2 + (uint64_t)xhalf * 64u;
-    uint32_t x_lane[4];
+    uint32_t x_lane[U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
         int64_t xg = m0 + xrow0 + 16 * u;
         if (xg > a.rows - 1)
             xg = a.rows - 1; // rows past the end read the last row (never stored)
@@ -261,7 +269,7 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
 
     // ---- W loader: LDS-direct loads.  One wave instruction brings 16 rows x 64 bytes (32 k) and
     // lands them in LDS as 1024 contiguous bytes, lane l at byte 16 l: row l / 4 of the 16, slot
-    // l % 4 of the row.  Instruction i of wave w covers rows 64 i + 16 w + 0..15 of the channel
+    // l % 4 of the row.  Instruction i of wave w covers rows 16 (NW i + w) + 0..15 of the channel
     // block.  Which 16-byte piece of its row a lane fetches is permuted (slot = piece xor g(row)) so
     // that the operand reads below, 16 rows at one piece index, fall into 16 different 16-byte bank
     // groups although rows are 64 bytes apart; g depends on the low four row bits only, i.e. on
@@ -272,7 +280,7 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
     if constexpr (NEDGE) {
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            int r = 64 * i + 16 * wave + (lane >> 2);
+            int r = 16 * NW * i + 16 * wave + (lane >> 2);
             if (n0 + r > a.Nout - 1)
                 r = a.Nout - 1 - n0;
             w_lane[i] = (uint32_t)r * K2 + (((uint32_t)lane & 3u) ^ w_g) * 16u;
@@ -282,12 +290,12 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
     }
     // stage at byte offset kbyte of the rows -> W buffer `buf`
     auto w_fetch = [&](int i, uint32_t kbyte, int buf) {
-        const lptr_t dst = lds + kWs0 + (uint32_t)buf * kWBuf + (uint32_t)(4 * i + wave) * 1024u;
+        const lptr_t dst = lds + kWs0 + (uint32_t)buf * kWBuf + (uint32_t)(NW * i + wave) * 1024u;
         gcptr_t src;
         if constexpr (NEDGE)
             src = (gcptr_t)(w_base + kbyte) + w_lane[i];
         else
-            src = (gcptr_t)(w_base + kbyte + (uint64_t)i * 64u * K2) + w_lane[0];
+            src = (gcptr_t)(w_base + kbyte + (uint64_t)i * (16u * NW) * K2) + w_lane[0];
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                          (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
@@ -347,17 +355,17 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
     uint32_t pp = rot; // the pair the matrix products work on
     coef_for(pp * 128u);
 
-    u32x4 xq[4]; // this lane's four 16-byte pieces (8 k each, of four rows) of the pair F works on next
+    u32x4 xq[U]; // this lane's 16-byte pieces (8 k each, of U rows) of the pair F works on next
 
     // ---- prologue: the first stage of W and F(first pair) into LDS, the first half of the second pair into registers
 #pragma unroll
     for (int i = 0; i < NT; ++i)
         w_fetch(i, pp * 128u, 0);
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < U; ++u)
         xq[u] = gload16(x_base + pp * 128u, x_lane[u]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
         u32x4 y;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -366,8 +374,9 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
     }
     {
         const uint32_t kp = next_pair(pp) * 128u;
-        xq[0] = gload16(x_base + kp, x_lane[0]);
-        xq[1] = gload16(x_base + kp, x_lane[1]);
+#pragma unroll
+        for (int u = 0; u < PPS; ++u)
+            xq[u] = gload16(x_base + kp, x_lane[u]);
         coef_for(kp);
     }
     __syncthreads();
@@ -384,7 +393,8 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
     auto stage = [&](auto Qc, uint32_t xsel_read, uint32_t xsel_write, uint32_t kbyte_next_stage,
                      uint32_t kbyte_refill) {
         constexpr int Q = decltype(Qc)::value;
-        constexpr int kPairsPerStep = (8 + NT - 1) / NT;
+        constexpr int kWords = 4 * PPS;                       // words (pairs of elements) F works on per stage and lane
+        constexpr int kPairsPerStep = (kWords + NT - 1) / NT;
         const uint32_t xb = xf_base + xsel_read + (uint32_t)Q * 64u;
         const uint32_t wb = wf_base + (uint32_t)Q * kWBuf;
         bf16x8 xf[MT];
@@ -397,11 +407,12 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
         wf[0] = lds_read16(wb);
         if constexpr (NT > 1)
             wf[1] = lds_read16(wb + 16u * kWRow);
-        // refill pieces 2 (1 - Q), 2 (1 - Q) + 1 of the x registers
-        keep_in_loop(x_lane[2 * (1 - Q)]);
-        keep_in_loop(x_lane[2 * (1 - Q) + 1]);
-        xq[2 * (1 - Q)] = gload16(x_base + kbyte_refill, x_lane[2 * (1 - Q)]);
-        xq[2 * (1 - Q) + 1] = gload16(x_base + kbyte_refill, x_lane[2 * (1 - Q) + 1]);
+        // refill the pieces that were consumed one stage ago
+#pragma unroll
+        for (int u = 0; u < PPS; ++u) {
+            keep_in_loop(x_lane[(1 - Q) * PPS + u]);
+            xq[(1 - Q) * PPS + u] = gload16(x_base + kbyte_refill, x_lane[(1 - Q) * PPS + u]);
+        }
         if constexpr (NEDGE) {
 #pragma unroll
             for (int i = 0; i < NT; ++i)
@@ -409,7 +420,7 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
         } else {
             keep_in_loop(w_lane[0]);
         }
-        u32x4 y0, y1;
+        u32x4 y[PPS];
         fence_schedule();
         static_for<0, NT>([&](auto ntc) {
             constexpr int nt = decltype(ntc)::value;
@@ -429,24 +440,23 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
             static_for<0, MT>([&](auto mtc) {
                 constexpr int mt = decltype(mtc)::value;
                 mfma_16x16x32<(nt * MT + mt) < kAgprTiles>(acc[nt][mt], wf[nt % 3], xf[mt]);
-                // F on this step's share: words nt, nt + NT, .. of the lane's 8 words of this stage
+                // F on this step's share: words nt, nt + NT, .. of the lane's words of this stage
                 static_for<0, kPairsPerStep>([&](auto ic) {
                     constexpr int j = nt + decltype(ic)::value * NT;
-                    if constexpr (j < 8)
-                        rational_piece<mt>(ps[decltype(ic)::value], xq[2 * Q + (j >> 2)][j & 3], c, res[decltype(ic)::value]);
+                    if constexpr (j < kWords)
+                        rational_piece<mt>(ps[decltype(ic)::value], xq[Q * PPS + (j >> 2)][j & 3], c, res[decltype(ic)::value]);
                 });
                 fence_schedule();
             });
             static_for<0, kPairsPerStep>([&](auto ic) {
                 constexpr int j = nt + decltype(ic)::value * NT;
-                if constexpr (j < 4)
-                    y0[j] = res[decltype(ic)::value];
-                else if constexpr (j < 8)
-                    y1[j - 4] = res[decltype(ic)::value];
+                if constexpr (j < kWords)
+                    y[j >> 2][j & 3] = res[decltype(ic)::value];
             });
         });
-        lds_write16(x_dst + xsel_write + (uint32_t)(2 * Q) * kXPieceStep, y0);
-        lds_write16(x_dst + xsel_write + (uint32_t)(2 * Q + 1) * kXPieceStep, y1);
+#pragma unroll
+        for (int u = 0; u < PPS; ++u)
+            lds_write16(x_dst + xsel_write + (uint32_t)(Q * PPS + u) * kXPieceStep, y[u]);
         __syncthreads();
     };
 
@@ -495,18 +505,36 @@ __global__ __launch_bounds__(kThreads, 1) void grkan_linear_fwd_kernel(const Lin
 // --------------------------------------------------------------------------
 using LinKernel = void (*)(const LinArgs);
 
-template <typename OUT> static LinKernel select_kernel(int nt, bool nedge)
+// Tile variants: (waves, 16-channel sub-tiles per wave) -> channels per workgroup
+//   (8, 6): 768  two waves per SIMD, the variant for wide layers
+//   (4, 6): 384
+//   (4, 3): 192  also with a partial last channel block
+struct Variant {
+    int nw, nt;
+    int bn() const { return 16 * nw * nt; }
+};
+
+static Variant pick_variant(int32_t D_out)
 {
-    switch (nt) {
-    case 12: return grkan_linear_fwd_kernel<12, OUT, false, 5, 4>;
-    case 6: return grkan_linear_fwd_kernel<6, OUT, false, 5, 4>;
-    case 3:
-        return nedge ? grkan_linear_fwd_kernel<3, OUT, true, 5, 4> : grkan_linear_fwd_kernel<3, OUT, false, 5, 4>;
-    }
+    if (D_out % 768 == 0)
+        return Variant{8, 6};
+    if (D_out % 384 == 0)
+        return Variant{4, 6};
+    return Variant{4, 3};
+}
+
+template <typename OUT> static LinKernel select_kernel(Variant v, bool nedge)
+{
+    if (v.nw == 8 && v.nt == 6)
+        return grkan_linear_fwd_kernel<8, 6, OUT, false, 5, 4>;
+    if (v.nw == 4 && v.nt == 6)
+        return grkan_linear_fwd_kernel<4, 6, OUT, false, 5, 4>;
+    if (v.nw == 4 && v.nt == 3)
+        return nedge ? grkan_linear_fwd_kernel<4, 3, OUT, true, 5, 4> : grkan_linear_fwd_kernel<4, 3, OUT, false, 5, 4>;
     return nullptr;
 }
 
-static size_t lds_bytes(int nt) { return (size_t)2 * kXBuf + (size_t)2 * (64 * nt) * kWRow; }
+static size_t lds_bytes(Variant v) { return (size_t)2 * kXBuf + (size_t)2 * v.bn() * kWRow; }
 
 // The kernels use more LDS than the default limit for dynamic shared memory; raise it once per
 // kernel and device.
@@ -565,13 +593,13 @@ extern "C" grkan_status_t grkan_linear_fwd(const void *x, const float *A, const 
     if (rows == 0)
         return GRKAN_OK;
 
-    const int nt = D_out % 768 == 0 ? 12 : (D_out % 384 == 0 ? 6 : 3);
-    const int bn = 64 * nt;
+    const Variant v = pick_variant(D_out);
+    const int bn = v.bn();
     const bool nedge = D_out % bn != 0;
-    const LinKernel kernel = out_dtype == GRKAN_BF16 ? select_kernel<bf16_out>(nt, nedge) : select_kernel<float>(nt, nedge);
+    const LinKernel kernel = out_dtype == GRKAN_BF16 ? select_kernel<bf16_out>(v, nedge) : select_kernel<float>(v, nedge);
     if (!kernel)
         return GRKAN_ERR_LAUNCH;
-    const size_t lds = lds_bytes(nt);
+    const size_t lds = lds_bytes(v);
     if (!allow_lds(reinterpret_cast<const void *>(kernel), lds))
         return GRKAN_ERR_LAUNCH;
 
@@ -594,7 +622,7 @@ extern "C" grkan_status_t grkan_linear_fwd(const void *x, const float *A, const 
     a.mblocks = (int32_t)mblocks;
     a.nblocks = (int32_t)nblocks;
     void *args[] = {&a};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)grid), dim3(kThreads),
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)grid), dim3(64 * v.nw),
                                          args, lds, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
 }
