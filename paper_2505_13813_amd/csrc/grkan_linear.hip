@@ -187,12 +187,16 @@ template <> struct OutPack<float> {
     {
         *(__attribute__((address_space(1))) f32x4 *)p = v;
     }
+    static __device__ __forceinline__ void to_lds(uint32_t addr, f32x4 v)
+    {
+        *(__attribute__((address_space(3))) f32x4 *)(uintptr_t)addr = v;
+    }
 };
 struct bf16_out {
     uint16_t bits;
 };
 template <> struct OutPack<bf16_out> {
-    static __device__ __forceinline__ void store(gptr_t p, f32x4 v)
+    static __device__ __forceinline__ u32x2 pack(f32x4 v)
     {
         f32x2 a, b;
         a[0] = v[0];
@@ -202,7 +206,15 @@ template <> struct OutPack<bf16_out> {
         u32x2 r;
         r[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
         r[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2));
-        *(__attribute__((address_space(1))) u32x2 *)p = r;
+        return r;
+    }
+    static __device__ __forceinline__ void store(gptr_t p, f32x4 v)
+    {
+        *(__attribute__((address_space(1))) u32x2 *)p = pack(v);
+    }
+    static __device__ __forceinline__ void to_lds(uint32_t addr, f32x4 v)
+    {
+        *(__attribute__((address_space(3))) u32x2 *)(uintptr_t)addr = pack(v);
     }
 };
 
@@ -481,21 +493,73 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
     // ---- epilogue: lane holds channels n0 + wave WN + nt 16 + (lane / 16) 4 + 0..3 of token m0 + mt 16 + lane % 16
-    const int32_t o_lane = n0 + wave * WN + (lane >> 4) * 4;
     constexpr int ES = (int)sizeof(OUT);
+    if constexpr (!NEDGE) {
+        // Through LDS, so that every store instruction of a wavefront covers 1 KB of one output row:
+        // stored straight from the accumulator layout a row would receive its cache lines in 32-byte
+        // parts, from different wavefronts at different times, and lines leave the L2 partly written
+        // (measured: 1.9 times the output's bytes written to memory).  The tile goes through in
+        // passes of as many 16-token sub-tiles as the operand buffers (no longer needed) hold.
+        constexpr int kRowB = (BN + 16) * ES; // the padding spreads 8 (float32: 4) tokens over the 64 banks
+        constexpr int kFit = (2 * kXBuf + 2 * kWBuf) / (16 * kRowB);
+        static_assert(kFit >= 1, "one 16-token sub-tile must fit the operand buffers");
+        constexpr int kPasses = (MT + kFit - 1) / kFit;
+        constexpr int MTP = (MT + kPasses - 1) / kPasses;
+        constexpr int CPR = BN * ES / 16; // 16-byte chunks per row
+        f32x4 bv[NT];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int32_t o = o_lane + nt * 16;
-        if (NEDGE && o >= a.Nout)
-            continue;
-        f32x4 bv = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (a.bias)
-            bv = *(const f32x4 *)(a.bias + o);
+        for (int nt = 0; nt < NT; ++nt) {
+            bv[nt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (a.bias)
+                bv[nt] = *(const f32x4 *)(a.bias + n0 + wave * WN + nt * 16 + (lane >> 4) * 4);
+        }
+        // every fetch into the operand buffers has landed (the last stages prefetch past the end of
+        // the walk, which wraps around) and every wavefront has read its last operands
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        const uint32_t lane_dst = lds0 + (uint32_t)(lane & 15) * kRowB + (uint32_t)(wave * WN + (lane >> 4) * 4) * ES;
+        char *const out_tile = a.out + ((int64_t)m0 * a.Nout + n0) * ES;
+        static_for<0, kPasses>([&](auto PASS) {
+            constexpr int P0 = PASS.value * MTP;
+            constexpr int NM = (MT - P0) < MTP ? (MT - P0) : MTP;
+            if constexpr (P0 > 0)
+                __syncthreads(); // the previous pass has been read out
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int64_t token = m0 + mt * 16 + (lane & 15);
-            if (token < a.rows)
-                OutPack<OUT>::store((gptr_t)(a.out + (token * a.Nout + o) * ES), acc[nt][mt] + bv);
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < NM; ++mt)
+                    OutPack<OUT>::to_lds(lane_dst + (uint32_t)(mt * 16) * kRowB + (uint32_t)(nt * 16) * ES,
+                                         acc[nt][P0 + mt] + bv[nt]);
+            __syncthreads();
+            constexpr int kChunks = NM * 16 * CPR;
+#pragma unroll 4
+            for (int c = tid; c < kChunks; c += 64 * NW) {
+                const int r = c / CPR;
+                const int col = c - r * CPR;
+                const int64_t trow = (int64_t)(P0 * 16 + r);
+                if (m0 + trow < a.rows) {
+                    const u32x4 v = *(const __attribute__((address_space(3))) u32x4 *)(uintptr_t)(
+                        lds0 + (uint32_t)r * kRowB + (uint32_t)col * 16u);
+                    *(__attribute__((address_space(1))) u32x4 *)(gptr_t)(out_tile + trow * a.Nout * ES + col * 16) = v;
+                }
+            }
+        });
+    } else {
+        const int32_t o_lane = n0 + wave * WN + (lane >> 4) * 4;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int32_t o = o_lane + nt * 16;
+            if (o >= a.Nout)
+                continue;
+            f32x4 bv = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (a.bias)
+                bv = *(const f32x4 *)(a.bias + o);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int64_t token = m0 + mt * 16 + (lane & 15);
+                if (token < a.rows)
+                    OutPack<OUT>::store((gptr_t)(a.out + (token * a.Nout + o) * ES), acc[nt][mt] + bv);
+            }
         }
     }
 }
