@@ -168,11 +168,11 @@ template <int S> __device__ __forceinline__ void rational_piece(PairState &t, ui
     } else if constexpr (S == 4) {
         t.p0 = fmaf(t.p0, t.x0, c.a[0]);
         t.p1 = fmaf(t.p1, t.x1, c.a[0]);
-        t.h0 = t.h0 * t.x0;
-        t.h1 = t.h1 * t.x1;
+        t.h0 = fmaf(fabsf(t.h0), fabsf(t.x0), 1.0f); // Q = 1 + |x h| (as q_of<false>)
+        t.h1 = fmaf(fabsf(t.h1), fabsf(t.x1), 1.0f);
     } else if constexpr (S == 5) {
-        t.h0 = __builtin_amdgcn_rcpf(1.0f + fabsf(t.h0));
-        t.h1 = __builtin_amdgcn_rcpf(1.0f + fabsf(t.h1));
+        t.h0 = __builtin_amdgcn_rcpf(t.h0);
+        t.h1 = __builtin_amdgcn_rcpf(t.h1);
     } else {
         f32x2 y;
         y[0] = t.p0 * t.h0;
@@ -281,8 +281,9 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
 
     // ---- W loader: LDS-direct loads.  One wave instruction brings 16 rows x 64 bytes (32 k) and
     // lands them in LDS as 1024 contiguous bytes, lane l at byte 16 l: row l / 4 of the 16, slot
-    // l % 4 of the row.  Instruction i of wave w covers rows 16 (NW i + w) + 0..15 of the channel
-    // block.  Which 16-byte piece of its row a lane fetches is permuted (slot = piece xor g(row)) so
+    // l % 4 of the row.  Instruction i of wave w covers rows WN w + 16 i + 0..15 of the channel
+    // block: the rows whose products this very wave computes, so that the weights need no barrier
+    // at all - a wave waits for its own loads and reads what they brought.  Which 16-byte piece of its row a lane fetches is permuted (slot = piece xor g(row)) so
     // that the operand reads below, 16 rows at one piece index, fall into 16 different 16-byte bank
     // groups although rows are 64 bytes apart; g depends on the low four row bits only, i.e. on
     // the lane.
@@ -292,22 +293,22 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     if constexpr (NEDGE) {
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
-            int r = 16 * NW * i + 16 * wave + (lane >> 2);
+            int r = WN * wave + 16 * i + (lane >> 2);
             if (n0 + r > a.Nout - 1)
                 r = a.Nout - 1 - n0;
             w_lane[i] = (uint32_t)r * K2 + (((uint32_t)lane & 3u) ^ w_g) * 16u;
         }
     } else {
-        w_lane[0] = (uint32_t)(16 * wave + (lane >> 2)) * K2 + (((uint32_t)lane & 3u) ^ w_g) * 16u;
+        w_lane[0] = (uint32_t)(WN * wave + (lane >> 2)) * K2 + (((uint32_t)lane & 3u) ^ w_g) * 16u;
     }
     // stage at byte offset kbyte of the rows -> W buffer `buf`
     auto w_fetch = [&](int i, uint32_t kbyte, int buf) {
-        const lptr_t dst = lds + kWs0 + (uint32_t)buf * kWBuf + (uint32_t)(NW * i + wave) * 1024u;
+        const lptr_t dst = lds + kWs0 + (uint32_t)buf * kWBuf + (uint32_t)(NT * wave + i) * 1024u;
         gcptr_t src;
         if constexpr (NEDGE)
             src = (gcptr_t)(w_base + kbyte) + w_lane[i];
         else
-            src = (gcptr_t)(w_base + kbyte + (uint64_t)i * (16u * NW) * K2) + w_lane[0];
+            src = (gcptr_t)(w_base + kbyte + (uint64_t)i * 16u * K2) + w_lane[0];
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                          (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
@@ -391,6 +392,7 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
             xq[u] = gload16(x_base + kp, x_lane[u]);
         coef_for(kp);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     // One stage: the matrix products of stage s = 2 p + Q from LDS.  Beside them: the next stage of
@@ -469,7 +471,13 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
 #pragma unroll
         for (int u = 0; u < PPS; ++u)
             lds_write16(x_dst + xsel_write + (uint32_t)(Q * PPS + u) * kXPieceStep, y[u]);
-        __syncthreads();
+        // The weights of the next stage were fetched by this wave for itself: waiting for its own
+        // loads is all the synchronisation they need.  The F values are shared: one barrier per pair,
+        // after its second stage (what this stage wrote is read from the next pair on, and the buffer
+        // it wrote to was last read in the pair before this one, which ended with a barrier).
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if constexpr (Q == 1)
+            __syncthreads();
     };
 
     uint32_t xsel = 0; // buffer the matrix products read
