@@ -8,25 +8,33 @@
 // bfloat16 and written to LDS, from where the matrix cores consume it.  F(x)
 // never exists in HBM.
 //
-// Geometry (one workgroup = 4 wavefronts, one per SIMD, up to 512 registers each):
-//   * a workgroup owns a tile of BM = 16 MT tokens x BN = 64 NT output channels
-//     and sweeps the whole contraction dimension K = D_in;
+// Geometry:
+//   * a workgroup of NW wavefronts (8: two per SIMD, or 4) owns a tile of BM = 112
+//     tokens x BN = 16 NW NT output channels (768 for the wide variant) and sweeps
+//     the whole contraction dimension K = D_in; one workgroup per compute unit;
 //   * wavefront w owns the 16 NT channels [16 NT w, 16 NT (w + 1)) of the tile for
-//     all BM tokens: MT x NT accumulators of v_mfma_f32_16x16x32_bf16, the
+//     all BM tokens: 7 x NT accumulators of v_mfma_f32_16x16x32_bf16, the
 //     weights as the row operand, F(x) as the column operand, so that a lane
 //     ends up with four consecutive output channels of one token;
-//   * W streams through LDS in stages of 32 k (64 bytes per row), double
-//     buffered through registers; x in pairs of stages (64 k = one 128-byte line
-//     per token), so that F of the next pair is computed while the matrix cores
-//     work on the current one; rows are padded by 16 bytes so that the 16 lanes
-//     of an operand read hit 16 different 16-byte bank groups;
-//   * the coefficient group of a stage is wave-uniform (d_g is a multiple of 32),
-//     so the coefficients live in scalar registers.
+//   * W streams through LDS in stages of 32 k (64 bytes per row) by LDS-direct
+//     loads, two buffers; every wave fetches exactly the rows it multiplies, so the
+//     weights need no barrier, only the wave's own load counter; rows are 64 bytes
+//     apart, unpadded, with the 16-byte pieces of a row permuted so that an operand
+//     read (16 rows at one piece index) hits 16 different bank groups;
+//   * x goes memory -> registers -> F -> LDS in pairs of stages (64 k = one
+//     128-byte line per token): F of the next pair is computed, in pieces placed
+//     between the matrix instructions, while the matrix cores work on the current
+//     one; one barrier per pair; rows padded by 16 bytes;
+//   * the coefficient group of a wave's share of a pair is wave-uniform (d_g is a
+//     multiple of 32), so the coefficients live in scalar registers;
+//   * the output tile leaves through LDS in whole rows (bias added, rounded).
 //
 // The tile is wide in the channel direction on purpose: every token-operand
-// element costs about 16 vector-ALU issue slots (F) once per workgroup that
-// consumes it, against BN / 512 matrix-core cycles per lane; only from
-// BN = 512 up does the matrix work outlast the evaluation of F.
+// element costs about 13 vector instructions (F) once per workgroup that
+// consumes it, and on this chip only about two vector instructions per matrix
+// instruction issue for free in its shadow (measured: each further one costs the
+// SIMD about 5 clocks).  At BN = 768 there are 2.1 per matrix instruction from F
+// alone; a narrower tile would be bound by the vector ALU, not the matrix cores.
 #include <hip/hip_runtime.h>
 
 #include <mutex>
@@ -123,6 +131,13 @@ template <bool AGPR> __device__ __forceinline__ void mfma_16x16x32(f32x4 &acc, c
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
     else
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
+// Waits until at most N of this wave's vector-memory loads (LDS-direct ones included) are in flight.
+template <int N> __device__ __forceinline__ void wait_loads()
+{
+    static_assert(N >= 0 && N < 64, "the counter has six bits");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 // Nothing may be moved across this point by the instruction scheduler.
@@ -343,8 +358,8 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     // memory path, into vector registers, with a wait on the vector-memory counter (and so on the
     // x and W loads just issued) in front of the first use.  (A quotient of an integer division is
     // formed by vector instructions, hence the readfirstlane.)
-    Coef<M, N> c;
-    auto coef_for = [&](uint32_t kbyte_pair) {
+    Coef<M, N> c, c_next;
+    auto coef_for = [&](Coef<M, N> &dst, uint32_t kbyte_pair) {
         const int g = __builtin_amdgcn_readfirstlane((int)((kbyte_pair / 2u + (uint32_t)xhalf * 32u) / (uint32_t)a.dgc));
         const float *pa = a.A + (size_t)g * (M + 1);
         const float *pb = a.B + (size_t)g * N;
@@ -359,14 +374,14 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
                      : "memory");
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            c.a[i] = a03[i];
-            c.b[i] = b14[i];
+            dst.a[i] = a03[i];
+            dst.b[i] = b14[i];
         }
-        c.a[4] = a45[0];
-        c.a[5] = a45[1];
+        dst.a[4] = a45[0];
+        dst.a[5] = a45[1];
     };
     uint32_t pp = rot; // the pair the matrix products work on
-    coef_for(pp * 128u);
+    coef_for(c, pp * 128u);
 
     u32x4 xq[U]; // this lane's 16-byte pieces (8 k each, of U rows) of the pair F works on next
 
@@ -390,27 +405,41 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
 #pragma unroll
         for (int u = 0; u < PPS; ++u)
             xq[u] = gload16(x_base + kp, x_lane[u]);
-        coef_for(kp);
+        coef_for(c, kp);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     // One stage: the matrix products of stage s = 2 p + Q from LDS.  Beside them: the next stage of
-    // W goes from memory straight into the other W buffer; one half of the x registers is refilled
-    // (the half that was consumed one stage ago); F is evaluated on the other half, which holds
-    // 16 k of pair p + 1, and written to the other x buffer.  Everything that is in flight has
-    // arrived when the stage ends (the barrier waits for the LDS-direct loads and, the load counter
-    // being in order, for all loads).  The loads issued during the last pair (for pairs that would
-    // come after it) wrap around to valid memory; what they bring is never consumed.
+    // W goes from memory straight into the other W buffer, one 16-row sub-tile per step; one half of
+    // the x registers is refilled (the half that was consumed one stage ago); F is evaluated on the
+    // other half, which holds 16 k of pair p + 1, and written to the other x buffer.
+    //
+    // Waiting.  A wave's loads complete in the order they were issued (x refill, then the sub-tiles
+    // 0 .. NT - 1 of a stage), and the weights are the wave's own, so a sub-tile is waited for just
+    // before its first read, two steps ahead of its use, by the number of younger loads that may stay
+    // in flight: there is no point in a stage at which all loads must have arrived, and a fetch has
+    // most of a stage to complete.  (Issued all at once at the start of a stage, or two per step, the
+    // fetches stalled the issuing wave for hundreds of cycles each: the path that forms the
+    // addresses of a 16-row gather is the narrow one.)  The F values are shared between the waves:
+    // one barrier per pair, after its second stage - what a stage writes is read from the next pair
+    // on, and the buffer it writes to was last read in the pair before, which ended with a barrier.
+    // The barrier is written in assembly, with a wait for this wave's LDS writes only: the
+    // compiler's own would wait for the loads in flight as well.  The loads issued during the last
+    // pair (for pairs that would come after it) wrap around to valid memory; what they bring is
+    // never consumed.
     // The order of the instructions is the one written here: every matrix instruction is followed
     // by a piece of F and a scheduling fence (see rational_piece).
     auto stage = [&](auto Qc, uint32_t xsel_read, uint32_t xsel_write, uint32_t kbyte_next_stage,
-                     uint32_t kbyte_refill) {
+                     uint32_t kbyte_refill, uint32_t kbyte_coef) {
         constexpr int Q = decltype(Qc)::value;
         constexpr int kWords = 4 * PPS;                       // words (pairs of elements) F works on per stage and lane
         constexpr int kPairsPerStep = (kWords + NT - 1) / NT;
         const uint32_t xb = xf_base + xsel_read + (uint32_t)Q * 64u;
         const uint32_t wb = wf_base + (uint32_t)Q * kWBuf;
+        // sub-tiles 0 and 1 of this stage (and the x refill issued before them) have arrived when
+        // at most the NT - 2 fetches after them are in flight
+        wait_loads<(NT > 2 ? NT - 2 : 0)>();
         bf16x8 xf[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -434,20 +463,21 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
         } else {
             keep_in_loop(w_lane[0]);
         }
+        // the coefficients F needs from the next pair on: fetched here, where the wave waits for its
+        // operands anyway, not after the barrier
+        if constexpr (Q == 1)
+            coef_for(c_next, kbyte_coef);
         u32x4 y[PPS];
         fence_schedule();
         static_for<0, NT>([&](auto ntc) {
             constexpr int nt = decltype(ntc)::value;
-            // the next stage of W, two fetches per step, so that the last is issued before half of
-            // this stage is over and has the rest of it to arrive (all of them at once at the start
-            // of the stage was measured 10 % slower: the wave then waits at the memory instructions
-            // before its first matrix instruction)
-            if constexpr (2 * nt < NT)
-                w_fetch(2 * nt, kbyte_next_stage, 1 - Q);
-            if constexpr (2 * nt + 1 < NT)
-                w_fetch(2 * nt + 1, kbyte_next_stage, 1 - Q);
-            if constexpr (nt + 2 < NT)
+            w_fetch(nt, kbyte_next_stage, 1 - Q);
+            if constexpr (nt + 2 < NT) {
+                // sub-tile nt + 2 of this stage: younger than it are the NT - 3 - nt fetches of the
+                // previous stage after it, this stage's x refill and its fetches 0 .. nt
+                wait_loads<NT - 2 + PPS>();
                 wf[(nt + 2) % 3] = lds_read16(wb + (uint32_t)(nt + 2) * 16u * kWRow);
+            }
             fence_schedule();
             PairState ps[kPairsPerStep];
             uint32_t res[kPairsPerStep];
@@ -471,13 +501,8 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
 #pragma unroll
         for (int u = 0; u < PPS; ++u)
             lds_write16(x_dst + xsel_write + (uint32_t)(Q * PPS + u) * kXPieceStep, y[u]);
-        // The weights of the next stage were fetched by this wave for itself: waiting for its own
-        // loads is all the synchronisation they need.  The F values are shared: one barrier per pair,
-        // after its second stage (what this stage wrote is read from the next pair on, and the buffer
-        // it wrote to was last read in the pair before this one, which ended with a barrier).
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if constexpr (Q == 1)
-            __syncthreads();
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     };
 
     uint32_t xsel = 0; // buffer the matrix products read
@@ -486,12 +511,12 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
         const uint32_t p2 = next_pair(p1);
         // first stage of the pair: fetch its second stage of W; refill pieces 2, 3 with the next pair;
         // F on pieces 0, 1 of the next pair
-        stage(std::integral_constant<int, 0>{}, xsel, kXBuf - xsel, pp * 128u + 64u, p1 * 128u);
+        stage(std::integral_constant<int, 0>{}, xsel, kXBuf - xsel, pp * 128u + 64u, p1 * 128u, 0u);
         // second stage: fetch the first stage of the next pair; refill pieces 0, 1 with the pair after
-        // it; F on pieces 2, 3 of the next pair
-        stage(std::integral_constant<int, 1>{}, xsel, kXBuf - xsel, p1 * 128u, p2 * 128u);
-        // F during the next pair works on the pair after it
-        coef_for(p2 * 128u);
+        // it; F on pieces 2, 3 of the next pair; the coefficients for F during the next pair, which
+        // works on the pair after it
+        stage(std::integral_constant<int, 1>{}, xsel, kXBuf - xsel, p1 * 128u, p2 * 128u, p2 * 128u);
+        c = c_next;
         xsel = kXBuf - xsel;
         pp = p1;
     }
