@@ -247,7 +247,8 @@ def cpu_baseline(cases):
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bfloat16 matrix peak, published
 
 
-def fused_linear_bench(torch, grkan, grkan_inputs, workload, launches, layers_wanted=("x2", "x1"), copy_calibration=False):
+def fused_linear_bench(torch, grkan, grkan_inputs, workload, launches, layers_wanted=("x2", "x1"), copy_calibration=False,
+                       preheat_ms=150.0):
     """The fused layer forward at the workload's layer shapes (x1 -> 4 D, x2 -> D / 4), bfloat16:
     grkan_linear_fwd against grkan_fwd + torch.addmm (the library matrix product) and the matrix
     product alone, each the mean of `launches` event-timed launches rotating over four input sets
@@ -281,6 +282,14 @@ def fused_linear_bench(torch, grkan, grkan_inputs, workload, launches, layers_wa
 
         res = {"shape": "[%d,%d] x [%d,%d]^T" % (rows, K, N, K), "GFLOP": flop / 1e9}
         for key, fn in (("fused", fused), ("grkan_fwd_plus_library_matmul", two_kernels), ("library_matmul_alone", product_only)):
+            # untimed: the clocks settle to this kernel's sustained state (the first ~100 launches after a
+            # change of load run up to 20 % slower), then 5 warm-up launches
+            t_pre, k = time.perf_counter(), 0
+            while (time.perf_counter() - t_pre) * 1e3 < preheat_ms:
+                for i in range(16):
+                    fn(k + i)
+                k += 16
+                torch.cuda.synchronize()
             for i in range(5):
                 fn(i)
             mean, med, mn, ci = launch_stats(torch, fn, launches)
@@ -301,7 +310,7 @@ def fused_linear_bench(torch, grkan, grkan_inputs, workload, launches, layers_wa
 
 def fused_linear_main(args, torch, grkan, grkan_inputs):
     res = fused_linear_bench(torch, grkan, grkan_inputs, args.workload, max(20, args.steps),
-                             copy_calibration=args.copy_calibration)
+                             copy_calibration=args.copy_calibration, preheat_ms=min(args.preheat_ms, 200.0))
     dom = res.get("fc2") or next(iter(res.values()))
     achieved = dom["fused"]["TFLOP/s"]
     traffic, traffic_src = measured_traffic("%s/bf16/linear_fwd_fc2" % args.workload)
@@ -605,7 +614,8 @@ def main():
         try:
             del layers, dom
             torch.cuda.empty_cache()
-            out["fused_layer_forward"] = fused_linear_bench(torch, grkan, grkan_inputs, args.workload, 20, ("x2",))
+            out["fused_layer_forward"] = fused_linear_bench(torch, grkan, grkan_inputs, args.workload, 20, ("x2",),
+                                                            preheat_ms=min(args.preheat_ms, 100.0))
         except grkan.GrkanError as exc:
             out["fused_layer_forward"] = {"error": str(exc)}
         layers = dom = None
