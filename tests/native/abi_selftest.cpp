@@ -1,6 +1,7 @@
 // Native self-test of the C ABI: a program with no Python and no torch in it
-// calls grkan_fwd / grkan_bwd through include/grkan.h on buffers it allocates
-// with the HIP runtime and compares every output with the fp64 C oracle
+// calls grkan_fwd / grkan_bwd / grkan_bwd_noalloc / grkan_linear_fwd through
+// include/grkan.h on buffers it allocates with the HIP runtime and compares
+// every output with the fp64 C oracle
 // (oracle/grkan_oracle.c, linked in as the checker) under the same error
 // measure as the Python parity tests.  Inputs come from a small counter-based
 // generator of its own (data only).  Built and run by tests/test_gpu_native.py.
@@ -13,6 +14,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <vector>
 
 #include "grkan.h"
@@ -24,6 +26,9 @@ int grkan_oracle_bwd(const double *x, const double *dy, const double *A, const d
                      double *dB, int64_t rows, int D, int G, int m, int n, int threads);
 int grkan_oracle_scales(const double *x, const double *dy, const double *A, const double *B, double *Sy, double *Sdx,
                         double *RA, double *RB, int64_t rows, int D, int G, int m, int n, int threads);
+int grkan_oracle_linear_fwd(const double *x, const double *A, const double *B, const double *W, const double *bias,
+                            double *out, int64_t rows, int D_in, int D_out, int G, int m, int n, int round_operand,
+                            int threads);
 }
 
 #define HIP_OK(call)                                                                                   \
@@ -103,12 +108,36 @@ static bool run_case(const Case &c, uint64_t seed)
     if (st == GRKAN_OK)
         st = grkan_bwd(d_x, d_dy, d_A, d_B, d_dx, d_dA, d_dB, d_ws, ws_bytes, c.rows, c.D, c.G, c.m, c.n, GRKAN_F32,
                        stream);
+    // the allocation-free variant into buffers of its own: must agree bit for bit
+    void *d_dx2;
+    float *d_dA2, *d_dB2;
+    HIP_OK(hipMalloc(&d_dx2, bytes ? bytes : 16));
+    HIP_OK(hipMalloc((void **)&d_dA2, na * sizeof(float)));
+    HIP_OK(hipMalloc((void **)&d_dB2, nb * sizeof(float)));
+    if (st == GRKAN_OK)
+        st = grkan_bwd_noalloc(d_x, d_dy, d_A, d_B, d_dx2, d_dA2, d_dB2, c.rows, c.D, c.G, c.m, c.n, GRKAN_F32, stream);
     if (st != GRKAN_OK) {
         std::printf("entry point failed: %s\n", grkan_status_string(st));
         return false;
     }
     HIP_OK(hipStreamSynchronize(stream));
     std::vector<float> y(M), dx(M), dA(na), dB(nb);
+    {
+        std::vector<float> dx2(M), dA2(na), dB2(nb);
+        HIP_OK(hipMemcpy(dx2.data(), d_dx2, bytes, hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(dA2.data(), d_dA2, na * sizeof(float), hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(dB2.data(), d_dB2, nb * sizeof(float), hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(dx.data(), d_dx, bytes, hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(dA.data(), d_dA, na * sizeof(float), hipMemcpyDeviceToHost));
+        HIP_OK(hipMemcpy(dB.data(), d_dB, nb * sizeof(float), hipMemcpyDeviceToHost));
+        if (std::memcmp(dx2.data(), dx.data(), bytes) || std::memcmp(dA2.data(), dA.data(), na * sizeof(float)) ||
+            std::memcmp(dB2.data(), dB.data(), nb * sizeof(float))) {
+            std::printf("FAIL grkan_bwd_noalloc differs from grkan_bwd\n");
+            return false;
+        }
+    }
+    for (void *p : {d_dx2, (void *)d_dA2, (void *)d_dB2})
+        HIP_OK(hipFree(p));
     HIP_OK(hipMemcpy(y.data(), d_y, bytes, hipMemcpyDeviceToHost));
     HIP_OK(hipMemcpy(dx.data(), d_dx, bytes, hipMemcpyDeviceToHost));
     HIP_OK(hipMemcpy(dA.data(), d_dA, na * sizeof(float), hipMemcpyDeviceToHost));
@@ -148,6 +177,110 @@ static bool run_case(const Case &c, uint64_t seed)
     return ok;
 }
 
+// ---- the fused layer, out = W F(x) + bias (bfloat16 x and W, float32 out) ----
+static uint16_t to_bf16(float v) // round to nearest even; data preparation only
+{
+    uint32_t u;
+    std::memcpy(&u, &v, 4);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+static float from_bf16(uint16_t h)
+{
+    const uint32_t u = (uint32_t)h << 16;
+    float v;
+    std::memcpy(&v, &u, 4);
+    return v;
+}
+
+struct LinCase {
+    int64_t rows;
+    int D_in, D_out, G;
+};
+
+static bool run_linear_case(const LinCase &c, uint64_t seed)
+{
+    const int m = 5, n = 4;
+    const int64_t MX = c.rows * c.D_in, MO = c.rows * c.D_out;
+    const int64_t MW = (int64_t)c.D_out * c.D_in;
+    Rng rng(seed);
+    std::vector<float> A(c.G * (m + 1)), B(c.G * n), bias(c.D_out);
+    for (int g = 0; g < c.G; ++g)
+        for (int i = 0; i <= m; ++i)
+            A[g * (m + 1) + i] = (float)((2.0 * rng.uniform() - 1.0) / (i + 1.0));
+    for (auto &b : B)
+        b = (float)(rng.uniform() - 0.5);
+    for (auto &b : bias)
+        b = (float)(0.1 * rng.normal());
+    std::vector<uint16_t> xb(MX), Wb(MW);
+    std::vector<double> xd(MX), Wd(MW);
+    for (int64_t e = 0; e < MX; ++e) {
+        xb[e] = to_bf16((float)rng.normal());
+        xd[e] = from_bf16(xb[e]);
+    }
+    const double wscale = 1.0 / std::sqrt((double)c.D_in);
+    for (int64_t e = 0; e < MW; ++e) {
+        Wb[e] = to_bf16((float)(wscale * rng.normal()));
+        Wd[e] = from_bf16(Wb[e]);
+    }
+    void *d_x, *d_W, *d_out;
+    float *d_A, *d_B, *d_bias;
+    HIP_OK(hipMalloc(&d_x, MX * 2));
+    HIP_OK(hipMalloc(&d_W, MW * 2));
+    HIP_OK(hipMalloc(&d_out, MO * 4));
+    HIP_OK(hipMalloc((void **)&d_A, A.size() * 4));
+    HIP_OK(hipMalloc((void **)&d_B, B.size() * 4));
+    HIP_OK(hipMalloc((void **)&d_bias, bias.size() * 4));
+    HIP_OK(hipMemcpy(d_x, xb.data(), MX * 2, hipMemcpyHostToDevice));
+    HIP_OK(hipMemcpy(d_W, Wb.data(), MW * 2, hipMemcpyHostToDevice));
+    HIP_OK(hipMemcpy(d_A, A.data(), A.size() * 4, hipMemcpyHostToDevice));
+    HIP_OK(hipMemcpy(d_B, B.data(), B.size() * 4, hipMemcpyHostToDevice));
+    HIP_OK(hipMemcpy(d_bias, bias.data(), bias.size() * 4, hipMemcpyHostToDevice));
+    hipStream_t stream;
+    HIP_OK(hipStreamCreate(&stream));
+    const grkan_status_t st = grkan_linear_fwd(d_x, d_A, d_B, d_W, d_bias, d_out, c.rows, c.D_in, c.D_out, c.G, m, n,
+                                               GRKAN_BF16, GRKAN_F32, stream);
+    if (st != GRKAN_OK) {
+        std::printf("grkan_linear_fwd failed: %s\n", grkan_status_string(st));
+        return false;
+    }
+    HIP_OK(hipStreamSynchronize(stream));
+    std::vector<float> out(MO);
+    HIP_OK(hipMemcpy(out.data(), d_out, MO * 4, hipMemcpyDeviceToHost));
+    HIP_OK(hipStreamDestroy(stream));
+    for (void *p : {d_x, d_W, d_out, (void *)d_A, (void *)d_B, (void *)d_bias})
+        HIP_OK(hipFree(p));
+
+    // checker: the definition in fp64, and the scale of a sum of D_in terms, R = sqrt(sum (W F)^2)
+    std::vector<double> Ad(A.begin(), A.end()), Bd(B.begin(), B.end()), bd(bias.begin(), bias.end());
+    std::vector<double> ref(MO), F(MX);
+    if (grkan_oracle_linear_fwd(xd.data(), Ad.data(), Bd.data(), Wd.data(), bd.data(), ref.data(), c.rows, c.D_in,
+                                c.D_out, c.G, m, n, 0, 8) ||
+        grkan_oracle_fwd(xd.data(), Ad.data(), Bd.data(), F.data(), c.rows, c.D_in, c.G, m, n, 8)) {
+        std::printf("oracle rejected the case\n");
+        return false;
+    }
+    double worst = 0.0;
+    for (int64_t r = 0; r < c.rows; ++r)
+        for (int o = 0; o < c.D_out; ++o) {
+            double ss = 0.0;
+            for (int k = 0; k < c.D_in; ++k) {
+                const double t = Wd[(int64_t)o * c.D_in + k] * F[r * c.D_in + k];
+                ss += t * t;
+            }
+            const double rv = ref[r * c.D_out + o];
+            const double e = std::fabs((double)out[r * c.D_out + o] - rv) / std::fmax(std::fmax(std::fabs(rv), std::sqrt(ss)), 1e-300);
+            if (!(e <= worst))
+                worst = std::isnan(e) ? INFINITY : e;
+        }
+    // operand rounding to bfloat16: 7.5 sigma of a sum of independent half-ulp errors (see the GPU tests)
+    const bool ok = worst <= 1.2e-2;
+    std::printf("%s layer rows %lld D_in %d D_out %d G %d: out %.2e\n", ok ? "ok  " : "FAIL", (long long)c.rows, c.D_in,
+                c.D_out, c.G, worst);
+    std::fflush(stdout);
+    return ok;
+}
+
 int main()
 {
     int n_dev = 0;
@@ -169,6 +302,13 @@ int main()
     uint64_t seed = 20250513;
     for (const Case &c : cases)
         all = run_case(c, seed++) && all;
+    const LinCase lin_cases[] = {
+        {250, 3072, 768, 8}, // the wide layer's shape: eight-wave tile, ragged token block
+        {333, 768, 384, 8},  // four-wave tile
+        {97, 256, 200, 4},   // partial last channel block
+    };
+    for (const LinCase &c : lin_cases)
+        all = run_linear_case(c, seed++) && all;
     std::printf(all ? "all cases within tolerance\n" : "SOME CASES FAILED\n");
     return all ? 0 : 1;
 }
