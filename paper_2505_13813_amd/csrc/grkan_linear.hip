@@ -233,6 +233,16 @@ template <> struct OutPack<bf16_out> {
     }
 };
 
+// Number of multiples of `period` in [lo, hi] (the x refills, one per stage start, among a range of steps).
+constexpr int multiples_in(int lo, int hi, int period)
+{
+    int n = 0;
+    for (int t = lo; t <= hi; ++t)
+        if (t % period == 0)
+            ++n;
+    return n;
+}
+
 // NW: wavefronts per workgroup (4: one per SIMD; 8: two per SIMD, each with half the registers, so
 // that one wavefront's waits at memory instructions and barriers are covered by the other's matrix
 // instructions).  NT: 16-channel sub-tiles per wavefront (BN = 16 NW NT).  NEDGE: the last channel
@@ -253,6 +263,14 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     constexpr int PPS = U / 2;   // ... of which it works on per stage
     constexpr int kWBuf = BN * kWRow;
     constexpr uint32_t kWs0 = 2 * kXBuf;
+    // How many 16-row sub-tiles a weight fetch runs ahead of the step that multiplies with it.  The two
+    // W buffers are a ring of 2 NT slots per wave, and a slot is free once the step that used it has
+    // been issued, so anything up to 2 NT - 2 is possible.  Measured at the wide layer (NT = 6),
+    // same box: 4 -> 152 us (every step waits for its sub-tile), 5 -> 147, 6 -> 149.7, 7 -> 147.4 (*),
+    // 8 -> 148.0 (*), 10 -> 152.7 (*) ((*) another box, where 6 gave 146.6): more requests in flight
+    // than needed slow everything down, as in the elementwise kernels.
+    constexpr int kAhead = NT == 6 ? 5 : NT;
+    constexpr int kStep0 = 4 * NT; // an arbitrary stage start, for counting in absolute steps
     extern __shared__ __align__(16) char smem[];
     const lptr_t lds = (lptr_t)smem;
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
@@ -353,32 +371,25 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     auto next_pair = [&](uint32_t pp) { return pp + 1u == (uint32_t)n_pairs ? 0u : pp + 1u; };
 
     // Coefficients of the group the wave's next F work lies in: wave-uniform, in scalar registers,
-    // reloaded once per pair.  Explicit scalar loads: inside the loop the compiler cannot show that
-    // nothing has written A and B since the kernel started and would fetch them through the vector
-    // memory path, into vector registers, with a wait on the vector-memory counter (and so on the
-    // x and W loads just issued) in front of the first use.  (A quotient of an integer division is
-    // formed by vector instructions, hence the readfirstlane.)
+    // reloaded once per pair.  They are read through the constant address space (nothing writes A
+    // and B while the kernel runs): the compiler then uses scalar loads and waits for them at their
+    // first use, a stage later.  Read through the generic pointers inside the loop, it cannot show
+    // that nothing has written them since the kernel started and would fetch them through the
+    // vector memory path, into vector registers, with a wait on the vector-memory counter (and so on
+    // the x and W loads just issued) in front of the first use.  (A quotient of an integer division
+    // is formed by vector instructions, hence the readfirstlane.)
+    typedef const __attribute__((address_space(4))) float *cfloat_ptr;
     Coef<M, N> c, c_next;
     auto coef_for = [&](Coef<M, N> &dst, uint32_t kbyte_pair) {
         const int g = __builtin_amdgcn_readfirstlane((int)((kbyte_pair / 2u + (uint32_t)xhalf * 32u) / (uint32_t)a.dgc));
-        const float *pa = a.A + (size_t)g * (M + 1);
-        const float *pb = a.B + (size_t)g * N;
-        f32x4 a03, b14;
-        f32x2 a45;
-        asm volatile("s_load_dwordx4 %0, %3, 0x0\n\t"
-                     "s_load_dwordx2 %1, %3, 0x10\n\t"
-                     "s_load_dwordx4 %2, %4, 0x0\n\t"
-                     "s_waitcnt lgkmcnt(0)"
-                     : "=&s"(a03), "=&s"(a45), "=&s"(b14)
-                     : "s"(pa), "s"(pb)
-                     : "memory");
+        const cfloat_ptr pa = (cfloat_ptr)(uintptr_t)(a.A + (size_t)g * (M + 1));
+        const cfloat_ptr pb = (cfloat_ptr)(uintptr_t)(a.B + (size_t)g * N);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            dst.a[i] = a03[i];
-            dst.b[i] = b14[i];
-        }
-        dst.a[4] = a45[0];
-        dst.a[5] = a45[1];
+        for (int i = 0; i <= M; ++i)
+            dst.a[i] = pa[i];
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            dst.b[i] = pb[i];
     };
     uint32_t pp = rot; // the pair the matrix products work on
     coef_for(c, pp * 128u);
@@ -387,8 +398,11 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
 
     // ---- prologue: the first stage of W and F(first pair) into LDS, the first half of the second pair into registers
 #pragma unroll
-    for (int i = 0; i < NT; ++i)
+    for (int i = 0; i < (kAhead < NT ? kAhead : NT); ++i)
         w_fetch(i, pp * 128u, 0);
+#pragma unroll
+    for (int i = 0; i < kAhead - NT; ++i)
+        w_fetch(i, pp * 128u + 64u, 1);
 #pragma unroll
     for (int u = 0; u < U; ++u)
         xq[u] = gload16(x_base + pp * 128u, x_lane[u]);
@@ -430,26 +444,33 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     // never consumed.
     // The order of the instructions is the one written here: every matrix instruction is followed
     // by a piece of F and a scheduling fence (see rational_piece).
-    auto stage = [&](auto Qc, uint32_t xsel_read, uint32_t xsel_write, uint32_t kbyte_next_stage,
+    bf16x8 xf[MT]; // token operands of a stage, one per 16-token sub-tile
+    bf16x8 wf[3];  // ring of weight operands
+    auto stage = [&](auto Qc, uint32_t xsel_read, uint32_t xsel_write, uint32_t kbyte_stage0, uint32_t kbyte_stage1, uint32_t kbyte_stage2,
                      uint32_t kbyte_refill, uint32_t kbyte_coef) {
         constexpr int Q = decltype(Qc)::value;
         constexpr int kWords = 4 * PPS;                       // words (pairs of elements) F works on per stage and lane
         constexpr int kPairsPerStep = (kWords + NT - 1) / NT;
         const uint32_t xb = xf_base + xsel_read + (uint32_t)Q * 64u;
         const uint32_t wb = wf_base + (uint32_t)Q * kWBuf;
-        // sub-tiles 0 and 1 of this stage (and the x refill issued before them) have arrived when
-        // at most the NT - 2 fetches after them are in flight
-        wait_loads<(NT > 2 ? NT - 2 : 0)>();
-        bf16x8 xf[MT];
+        // The second stage of a pair finds its first operands already on their way: the first stage
+        // reads them during its last two steps, each register as soon as its last use has been
+        // issued (the x values of the pair are all in LDS, the weights are the wave's own).  The
+        // first stage of a pair follows a barrier and reads its operands here.
+        constexpr bool kHandOver = NT == 6; // the register ring below frees slots 0 and 1 in steps NT - 2 and NT - 1
+        if constexpr (!(kHandOver && Q == 1)) {
+            // sub-tiles 0 and 1 of this stage have arrived when at most the loads issued after the
+            // fetch of sub-tile 1 are in flight: kAhead - 2 fetches and the x refills between them
+            wait_loads<kAhead - 2 + PPS * multiples_in(kStep0 + 1 - kAhead + 1, kStep0 - 1, NT)>();
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-            xf[mt] = lds_read16(xb + (uint32_t)mt * 16u * kXPitch);
-        // weight operands two steps ahead of their use (an LDS read takes longer than the 7 matrix
-        // instructions of one step)
-        bf16x8 wf[3];
-        wf[0] = lds_read16(wb);
-        if constexpr (NT > 1)
-            wf[1] = lds_read16(wb + 16u * kWRow);
+            for (int mt = 0; mt < MT; ++mt)
+                xf[mt] = lds_read16(xb + (uint32_t)mt * 16u * kXPitch);
+            // weight operands two steps ahead of their use (an LDS read takes longer than the 7 matrix
+            // instructions of one step)
+            wf[0] = lds_read16(wb);
+            if constexpr (NT > 1)
+                wf[1] = lds_read16(wb + 16u * kWRow);
+        }
         // refill the pieces that were consumed one stage ago
 #pragma unroll
         for (int u = 0; u < PPS; ++u) {
@@ -463,20 +484,28 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
         } else {
             keep_in_loop(w_lane[0]);
         }
-        // the coefficients F needs from the next pair on: fetched here, where the wave waits for its
-        // operands anyway, not after the barrier
-        if constexpr (Q == 1)
-            coef_for(c_next, kbyte_coef);
         u32x4 y[PPS];
         fence_schedule();
         static_for<0, NT>([&](auto ntc) {
             constexpr int nt = decltype(ntc)::value;
-            w_fetch(nt, kbyte_next_stage, 1 - Q);
+            // the fetch of this step: the sub-tile kAhead steps on, into the slot of the ring whose
+            // sub-tile was multiplied two steps ago
+            if constexpr (nt + kAhead < NT)
+                w_fetch(nt + kAhead, kbyte_stage0, Q);
+            else if constexpr (nt + kAhead < 2 * NT)
+                w_fetch(nt + kAhead - NT, kbyte_stage1, 1 - Q);
+            else
+                w_fetch(nt + kAhead - 2 * NT, kbyte_stage2, Q);
+            // A sub-tile is read two steps ahead of its use; its fetch was issued kAhead steps before
+            // that use, and younger than it are the kAhead - 2 fetches since and the x refills of the
+            // stage starts in between.
             if constexpr (nt + 2 < NT) {
-                // sub-tile nt + 2 of this stage: younger than it are the NT - 3 - nt fetches of the
-                // previous stage after it, this stage's x refill and its fetches 0 .. nt
-                wait_loads<NT - 2 + PPS>();
+                wait_loads<kAhead - 2 + PPS * multiples_in(kStep0 + nt + 2 - kAhead + 1, kStep0 + nt, NT)>();
                 wf[(nt + 2) % 3] = lds_read16(wb + (uint32_t)(nt + 2) * 16u * kWRow);
+            } else if constexpr (kHandOver && Q == 0) {
+                // sub-tile nt + 2 - NT (0, then 1) of the next stage
+                wait_loads<kAhead - 2 + PPS * multiples_in(kStep0 + nt + 2 - kAhead + 1, kStep0 + nt, NT)>();
+                wf[(nt + 2) % 3] = lds_read16(wf_base + (uint32_t)(1 - Q) * kWBuf + (uint32_t)(nt + 2 - NT) * 16u * kWRow);
             }
             fence_schedule();
             PairState ps[kPairsPerStep];
@@ -484,6 +513,14 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
             static_for<0, MT>([&](auto mtc) {
                 constexpr int mt = decltype(mtc)::value;
                 mfma_16x16x32<(nt * MT + mt) < kAgprTiles>(acc[nt][mt], wf[nt % 3], xf[mt]);
+                // The coefficients F needs from the next pair on are requested right after the first
+                // matrix instruction of the pair: scalar loads and LDS reads share a counter that can
+                // only be waited on as a whole while a scalar load is in flight, and the next wait
+                // for an LDS operand is two steps away.
+                if constexpr (Q == 0 && nt == 0 && mt == 0)
+                    coef_for(c_next, kbyte_coef);
+                if constexpr (kHandOver && Q == 0 && nt == NT - 1)
+                    xf[mt] = lds_read16(xf_base + xsel_read + 64u + (uint32_t)mt * 16u * kXPitch);
                 // F on this step's share: words nt, nt + NT, .. of the lane's words of this stage
                 static_for<0, kPairsPerStep>([&](auto ic) {
                     constexpr int j = nt + decltype(ic)::value * NT;
@@ -509,13 +546,13 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     for (int32_t p = 0; p < n_pairs; ++p) {
         const uint32_t p1 = next_pair(pp);
         const uint32_t p2 = next_pair(p1);
-        // first stage of the pair: fetch its second stage of W; refill pieces 2, 3 with the next pair;
-        // F on pieces 0, 1 of the next pair
-        stage(std::integral_constant<int, 0>{}, xsel, kXBuf - xsel, pp * 128u + 64u, p1 * 128u, 0u);
-        // second stage: fetch the first stage of the next pair; refill pieces 0, 1 with the pair after
-        // it; F on pieces 2, 3 of the next pair; the coefficients for F during the next pair, which
-        // works on the pair after it
-        stage(std::integral_constant<int, 1>{}, xsel, kXBuf - xsel, p1 * 128u, p2 * 128u, p2 * 128u);
+        // first stage of the pair (the weight fetches run kAhead sub-tiles ahead, into the next stage
+        // and the one after it): refill pieces 2, 3 with the next pair; F on pieces 0, 1 of the next pair
+        stage(std::integral_constant<int, 0>{}, xsel, kXBuf - xsel, pp * 128u, pp * 128u + 64u, p1 * 128u, p1 * 128u, p2 * 128u);
+        // second stage: refill pieces 0, 1 with the pair after the next; F on pieces 2, 3 of the next
+        // pair.  (The coefficients requested in the first stage
+        // are for F during the next pair, which works on the pair after it.)
+        stage(std::integral_constant<int, 1>{}, xsel, kXBuf - xsel, pp * 128u + 64u, p1 * 128u, p1 * 128u + 64u, p2 * 128u, 0u);
         c = c_next;
         xsel = kXBuf - xsel;
         pp = p1;
