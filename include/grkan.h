@@ -57,7 +57,8 @@ typedef enum {
     GRKAN_ERR_WORKSPACE = 5, /* workspace missing or smaller than required */
     GRKAN_ERR_DTYPE = 6,     /* unknown grkan_dtype_t */
     GRKAN_ERR_LAUNCH = 7,    /* the HIP runtime rejected a launch or query */
-    GRKAN_ERR_UNSUPPORTED = 8, /* shape outside what the kernels index (see grkan_plan) */
+    GRKAN_ERR_UNSUPPORTED = 8, /* shape outside what the kernels index (see grkan_plan), or outside the shapes and
+                                  types grkan_linear_fwd is built for */
     GRKAN_ERR_SCRATCH_LIMIT = 9 /* grkan_bwd_noalloc: the shape needs more workspace than the built-in scratch */
 } grkan_status_t;
 

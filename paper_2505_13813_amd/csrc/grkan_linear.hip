@@ -641,7 +641,8 @@ using LinKernel = void (*)(const LinArgs);
 
 // Tile variants: (waves, 16-channel sub-tiles per wave) -> channels per workgroup
 //   (8, 6): 768  two waves per SIMD, the variant for wide layers
-//   (4, 6): 384
+//   (8, 3): 384  two waves per SIMD (one wave per SIMD with six sub-tiles was 12 % slower: a single
+//                 wave cannot cover its own waits)
 //   (4, 3): 192  also with a partial last channel block
 struct Variant {
     int nw, nt;
@@ -653,7 +654,7 @@ static Variant pick_variant(int32_t D_out)
     if (D_out % 768 == 0)
         return Variant{8, 6};
     if (D_out % 384 == 0)
-        return Variant{4, 6};
+        return Variant{8, 3};
     return Variant{4, 3};
 }
 
@@ -661,8 +662,8 @@ template <typename OUT> static LinKernel select_kernel(Variant v, bool nedge)
 {
     if (v.nw == 8 && v.nt == 6)
         return grkan_linear_fwd_kernel<8, 6, OUT, false, 5, 4>;
-    if (v.nw == 4 && v.nt == 6)
-        return grkan_linear_fwd_kernel<4, 6, OUT, false, 5, 4>;
+    if (v.nw == 8 && v.nt == 3)
+        return grkan_linear_fwd_kernel<8, 3, OUT, false, 5, 4>;
     if (v.nw == 4 && v.nt == 3)
         return nedge ? grkan_linear_fwd_kernel<4, 3, OUT, true, 5, 4> : grkan_linear_fwd_kernel<4, 3, OUT, false, 5, 4>;
     return nullptr;

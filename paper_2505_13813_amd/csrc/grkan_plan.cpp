@@ -322,7 +322,8 @@ extern "C" const char *grkan_status_string(grkan_status_t s)
     case GRKAN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case GRKAN_ERR_DTYPE: return "unknown dtype";
     case GRKAN_ERR_LAUNCH: return "HIP launch or query failed";
-    case GRKAN_ERR_UNSUPPORTED: return "shape too large for the kernels' index arithmetic";
+    case GRKAN_ERR_UNSUPPORTED:
+        return "shape or type outside what the kernels cover (index range; grkan_linear_fwd: see its conditions)";
     case GRKAN_ERR_SCRATCH_LIMIT: return "the shape needs more workspace than the 4 MiB scratch of grkan_bwd_noalloc";
     }
     return "unknown status";

@@ -304,7 +304,7 @@ int main()
         all = run_case(c, seed++) && all;
     const LinCase lin_cases[] = {
         {250, 3072, 768, 8}, // the wide layer's shape: eight-wave tile, ragged token block
-        {333, 768, 384, 8},  // four-wave tile
+        {333, 768, 384, 8},  // the 384-channel tile
         {97, 256, 200, 4},   // partial last channel block
     };
     for (const LinCase &c : lin_cases)

@@ -106,9 +106,9 @@ SHAPES = [
     (113, 768, 192, 8),         # one token past a block, BN = 192
     (1, 64, 4, 2),              # smallest shape: one row, one pair of stages, a sliver of a channel block
     (17, 128, 200, 4),          # partial channel block (edge variant), d_g = 32
-    (225, 3072, 768, 8),        # KAT-B fc2 contraction length, two channel blocks of 384
+    (225, 3072, 768, 8),        # KAT-B fc2 contraction length, one channel block of 768 (eight waves)
     (130, 192, 768, 2),         # d_g = 96 with D_in = 192
-    (112, 256, 1152, 8),        # exactly one token block, three channel blocks
+    (112, 256, 1152, 8),        # exactly one token block, three channel blocks of 384
     (500, 64, 64, 1),           # one group, short contraction
     (97, 1536, 388, 48),        # d_g = 32: the coefficient group changes every stage; edge block
 ]
