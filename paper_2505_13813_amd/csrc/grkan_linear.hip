@@ -723,7 +723,8 @@ extern "C" grkan_status_t grkan_linear_fwd(const void *x, const float *A, const 
     // a lane stores four consecutive channels
     if (D_in % 64 != 0 || dg % 32 != 0 || D_out % 4 != 0)
         return GRKAN_ERR_UNSUPPORTED;
-    if (rows > (INT64_MAX / 8) / (D_in > D_out ? D_in : D_out) || (int64_t)D_in * 2 * 128 >= ((int64_t)1 << 32))
+    // 32-bit lane offsets inside a tile: up to 128 rows of x and up to 768 rows of W, D_in * 2 bytes apart
+    if (rows > (INT64_MAX / 8) / (D_in > D_out ? D_in : D_out) || (int64_t)D_in * 2 * 768 >= ((int64_t)1 << 32))
         return GRKAN_ERR_UNSUPPORTED;
     if (rows == 0)
         return GRKAN_OK;
