@@ -193,7 +193,7 @@ grkan_status_t grkan_bwd(const void *x, const void *dy, const float *A, const fl
  *   out  DEVICE, [rows, D_out] of out_dtype (GRKAN_BF16: rounded to nearest even; GRKAN_F32), 16-byte
  *        aligned; must not overlap x or W
  *
- * Shapes: D_in a multiple of 64 (and below 2^21), d_g a multiple of 32 and D_out
+ * Shapes: D_in a multiple of 64 (and below 2^32 / 1536), d_g a multiple of 32 and D_out
  * a multiple of 4 (of the paper's model table: both layers of KAT-B and the second
  * layer of KAT-T and KAT-S; their first layers have groups of 24 and 48 channels);
  * anything else returns GRKAN_ERR_UNSUPPORTED and the caller runs grkan_fwd
