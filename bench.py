@@ -627,8 +627,8 @@ def main():
         try:
             del layers, dom
             torch.cuda.empty_cache()
-            out["fused_layer_forward"] = fused_linear_bench(torch, grkan, grkan_inputs, args.workload, 20, ("x2",),
-                                                            preheat_ms=min(args.preheat_ms, 100.0))
+            out["fused_layer_forward"] = fused_linear_bench(torch, grkan, grkan_inputs, args.workload, 50, ("x2",),
+                                                            preheat_ms=min(args.preheat_ms, 200.0))
         except grkan.GrkanError as exc:
             out["fused_layer_forward"] = {"error": str(exc)}
         layers = dom = None
