@@ -121,6 +121,29 @@ def test_fused_layer_shapes(oracle, rows, D_in, D_out, G, out_dtype):
     check(oracle, case, out_dtype, "%dx%d -> %d G=%d" % (rows, D_in, D_out, G))
 
 
+def _random_shapes(count, seed):
+    """Seeded shapes inside what the fused kernel covers: D_in a multiple of 64, d_g of 32, D_out of 4."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        rows = int(rng.integers(1, 400))
+        D_in = 64 * int(rng.integers(1, 17))
+        groups = [g for g in (1, 2, 3, 4, 6, 8, 12, 16, 24, 32) if D_in % g == 0 and (D_in // g) % 32 == 0]
+        G = int(rng.choice(groups))
+        kind = int(rng.integers(0, 4))  # whole blocks of each tile variant, or anything a multiple of 4
+        D_out = [192 * int(rng.integers(1, 5)), 384 * int(rng.integers(1, 4)), 768 * int(rng.integers(1, 3)),
+                 4 * int(rng.integers(1, 400))][kind]
+        shapes.append((rows, D_in, D_out, G))
+    return shapes
+
+
+@pytest.mark.parametrize("rows,D_in,D_out,G", _random_shapes(12, 20250527))
+def test_fused_layer_random_shapes(oracle, rows, D_in, D_out, G):
+    # every tile variant, full and partial channel blocks, one to four token blocks, odd group counts
+    case = custom_linear_case(rows + 3 * D_in + 5 * D_out + G, rows, D_in, D_out, G, bias=bool(D_out % 8))
+    check(oracle, case, "bf16" if rows % 2 else "f32", "random %dx%d -> %d G=%d" % (rows, D_in, D_out, G))
+
+
 def test_fused_layer_identity_rational_is_a_plain_matrix_product(oracle):
     # A = e_1, B = 0 (the paper's first-layer initialisation): F(x) = x exactly, also after rounding
     # (x is bfloat16 already), so the kernel must agree with an fp64 product to float32 accumulation accuracy
