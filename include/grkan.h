@@ -209,6 +209,33 @@ grkan_status_t grkan_linear_fwd(const void *x, const float *A, const float *B, c
                                 void *hip_stream);
 
 /*
+ * The same layer with the weights in a packed copy, for callers whose weights do
+ * not change between calls (inference): the kernel's weight fetches then read
+ * whole cache lines in sequence (5 - 8 % of the layer's time at the paper's wide
+ * layer).  Results are bit-identical to grkan_linear_fwd (same arithmetic, same
+ * summation order).
+ *
+ * grkan_linear_packed_w_bytes: size of the packed copy of a [D_out, D_in]
+ *   bfloat16 matrix, or 0 if grkan_linear_fwd does not cover the shape.
+ * grkan_linear_pack_w: writes it (one small kernel on hip_stream).
+ *   W  DEVICE, bfloat16 [D_out, D_in] row-major, 16-byte aligned
+ *   Wp DEVICE, grkan_linear_packed_w_bytes(D_in, D_out) bytes, 16-byte aligned, caller-owned.
+ *   Layout: T = D_out rounded up to whole channel blocks of the kernel's tile, in
+ *   units of 16 rows; for stage s (32 consecutive k), tile t and l = 0..63 the 16
+ *   bytes at ((s T + t) 64 + l) 16 are row 16 t + l / 4, bytes
+ *   64 s + 16 ((l mod 4) xor g) .. + 15 of W, g = ((l >> 4) xor (l >> 3)) and 3;
+ *   rows past D_out are zeros.  The layout is tied to this library's build.
+ * grkan_linear_fwd_packed: as grkan_linear_fwd with Wp in place of W.
+ */
+size_t grkan_linear_packed_w_bytes(int32_t D_in, int32_t D_out);
+grkan_status_t grkan_linear_pack_w(const void *W, void *Wp, int32_t D_in, int32_t D_out, void *hip_stream);
+grkan_status_t grkan_linear_fwd_packed(const void *x, const float *A, const float *B, const void *Wp,
+                                       const float *bias, void *out,
+                                       int64_t rows, int32_t D_in, int32_t D_out, int32_t G,
+                                       int32_t m, int32_t n, grkan_dtype_t io, grkan_dtype_t out_dtype,
+                                       void *hip_stream);
+
+/*
  * grkan_bwd for callers that cannot allocate device memory or pass a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, results and kernels as grkan_bwd (bit-identical

@@ -17,7 +17,9 @@ from .binding import (  # noqa: F401
     grkan_bwd_raw,
     grkan_bwd_workspace_bytes,
     grkan_fwd,
+    PackedWeight,
     grkan_linear_fwd,
+    grkan_linear_pack_w,
     grkan_fwd_raw,
     load_library,
     plan,

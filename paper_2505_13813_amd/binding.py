@@ -87,6 +87,12 @@ def load_library():
     lib.grkan_bwd.restype = ctypes.c_int
     lib.grkan_linear_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, ctypes.c_int, ctypes.c_int, vp]
     lib.grkan_linear_fwd.restype = ctypes.c_int
+    lib.grkan_linear_fwd_packed.argtypes = lib.grkan_linear_fwd.argtypes
+    lib.grkan_linear_fwd_packed.restype = ctypes.c_int
+    lib.grkan_linear_packed_w_bytes.argtypes = [i32, i32]
+    lib.grkan_linear_packed_w_bytes.restype = ctypes.c_size_t
+    lib.grkan_linear_pack_w.argtypes = [vp, vp, i32, i32, vp]
+    lib.grkan_linear_pack_w.restype = ctypes.c_int
     lib.grkan_bwd_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i32, ctypes.c_int, vp]
     lib.grkan_bwd_noalloc.restype = ctypes.c_int
     lib.grkan_alg1_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, vp]
@@ -257,17 +263,52 @@ def grkan_bwd(x, dy, A, B, workspace: Optional["torch.Tensor"] = None, out=None,
     return dx, dA, dB
 
 
+class PackedWeight:
+    """The packed copy grkan_linear_pack_w makes of a [D_out, D_in] bfloat16 weight matrix (opaque
+    bytes on the device) with the shape it was made from."""
+
+    def __init__(self, data, D_out: int, D_in: int):
+        self.data, self.D_out, self.D_in = data, int(D_out), int(D_in)
+
+
+def grkan_linear_pack_w(W, stream=None) -> PackedWeight:
+    """Packed copy of the weights for grkan_linear_fwd (weights that stay the same between calls):
+    the layer kernel then fetches them in whole cache lines.  One small kernel; allocates the copy."""
+    import torch
+
+    if W.dtype != torch.bfloat16 or W.dim() != 2 or not W.is_contiguous() or not W.is_cuda:
+        raise ValueError("W must be a contiguous bfloat16 [D_out, D_in] tensor on the GPU")
+    D_out, D_in = int(W.shape[0]), int(W.shape[1])
+    need = int(load_library().grkan_linear_packed_w_bytes(D_in, D_out))
+    if need == 0:
+        raise GrkanError(8, "grkan_linear_packed_w_bytes")
+    data = torch.empty(need, dtype=torch.uint8, device=W.device)
+    st = int(load_library().grkan_linear_pack_w(W.data_ptr(), data.data_ptr(), D_in, D_out, _stream_ptr(stream)))
+    if st:
+        raise GrkanError(st, "grkan_linear_pack_w")
+    return PackedWeight(data, D_out, D_in)
+
+
 def grkan_linear_fwd(x, A, B, W, bias=None, out=None, out_dtype=None, stream=None):
-    """out = F(x) W^T (+ bias): the GR-KAN layer in one kernel (Eq. "GR_KAN").  x and W
-    bfloat16, bias float32 or None, out bfloat16 (default) or float32."""
+    """out = F(x) W^T (+ bias): the GR-KAN layer in one kernel (Eq. "GR_KAN").  x bfloat16; W a
+    bfloat16 [D_out, D_in] tensor or its PackedWeight; bias float32 or None; out bfloat16 (default)
+    or float32."""
     import torch
 
     rows, D_in, G = _check(x, A, B)
-    if x.dtype != torch.bfloat16 or W.dtype != torch.bfloat16:
-        raise TypeError("x and W must be bfloat16")
-    if W.dim() != 2 or W.shape[1] != D_in or not W.is_contiguous() or W.device != x.device:
-        raise ValueError("W must be a contiguous [D_out, D_in] tensor on the device of x")
-    D_out = int(W.shape[0])
+    packed = isinstance(W, PackedWeight)
+    if packed:
+        if x.dtype != torch.bfloat16:
+            raise TypeError("x must be bfloat16")
+        if W.D_in != D_in or W.data.device != x.device:
+            raise ValueError("the packed weights were made for another D_in or device")
+        D_out, w_ptr = W.D_out, W.data.data_ptr()
+    else:
+        if x.dtype != torch.bfloat16 or W.dtype != torch.bfloat16:
+            raise TypeError("x and W must be bfloat16")
+        if W.dim() != 2 or W.shape[1] != D_in or not W.is_contiguous() or W.device != x.device:
+            raise ValueError("W must be a contiguous [D_out, D_in] tensor on the device of x")
+        D_out, w_ptr = int(W.shape[0]), W.data_ptr()
     if bias is not None and (bias.dtype != torch.float32 or bias.shape != (D_out,) or not bias.is_contiguous()
                              or bias.device != x.device):
         raise ValueError("bias must be a contiguous float32 [D_out] tensor on the device of x")
@@ -276,12 +317,14 @@ def grkan_linear_fwd(x, A, B, W, bias=None, out=None, out_dtype=None, stream=Non
     if (out.dtype not in (torch.bfloat16, torch.float32) or out.shape != x.shape[:-1] + (D_out,)
             or not out.is_contiguous() or out.device != x.device):
         raise ValueError("out must be a contiguous bfloat16 or float32 [..., D_out] tensor on the device of x")
-    st = int(load_library().grkan_linear_fwd(
-        x.data_ptr(), A.data_ptr(), B.data_ptr(), W.data_ptr(), bias.data_ptr() if bias is not None else None,
+    lib = load_library()
+    entry = lib.grkan_linear_fwd_packed if packed else lib.grkan_linear_fwd
+    st = int(entry(
+        x.data_ptr(), A.data_ptr(), B.data_ptr(), w_ptr, bias.data_ptr() if bias is not None else None,
         out.data_ptr(), rows, D_in, D_out, G, int(A.shape[1]) - 1, int(B.shape[1]), GRKAN_BF16,
         GRKAN_BF16 if out.dtype == torch.bfloat16 else GRKAN_F32, _stream_ptr(stream)))
     if st:
-        raise GrkanError(st, "grkan_linear_fwd")
+        raise GrkanError(st, "grkan_linear_fwd_packed" if packed else "grkan_linear_fwd")
     return out
 
 

@@ -77,6 +77,7 @@ struct LinArgs {
     int32_t dgc;       // channels per coefficient group (a multiple of 32)
     int32_t mblocks;   // ceil(rows / BM)
     int32_t nblocks;   // ceil(Nout / BN)
+    int32_t wtiles;    // packed W only: 16-row tiles per stage, nblocks * BN / 16
 };
 
 __device__ __forceinline__ uint64_t uniform_u64(uint64_t v)
@@ -247,7 +248,12 @@ constexpr int multiples_in(int lo, int hi, int period)
 // that one wavefront's waits at memory instructions and barriers are covered by the other's matrix
 // instructions).  NT: 16-channel sub-tiles per wavefront (BN = 16 NW NT).  NEDGE: the last channel
 // block may be partial (weight rows are clamped, stores predicated).
-template <int NW, int NT, typename OUT, bool NEDGE, int M, int N>
+//
+// PACKED: a.W is the copy grkan_linear_pack_w makes of the weights, in which the 1 KB a weight fetch
+// brings (16 rows x 32 k, pieces already permuted) is contiguous: the fetch then reads eight whole
+// cache lines in sequence instead of sixteen half lines D_in * 2 bytes apart (5 - 8 % of the kernel's
+// time at the wide layer).  Rows past Nout are zeros there.
+template <int NW, int NT, typename OUT, bool NEDGE, bool PACKED, int M, int N>
 __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinArgs a)
 {
     static_assert(M == 5 && N == 4 && kMT == 7, "rational_piece is written for degrees (5, 4) and 7-tile steps");
@@ -269,7 +275,9 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     // same box: 4 -> 152 us (every step waits for its sub-tile), 5 -> 147, 6 -> 149.7, 7 -> 147.4 (*),
     // 8 -> 148.0 (*), 10 -> 152.7 (*) ((*) another box, where 6 gave 146.6): more requests in flight
     // than needed slow everything down, as in the elementwise kernels.
-    constexpr int kAhead = NT == 6 ? 5 : NT;
+    // With the packed weights a fetch is cheaper on the memory side and one step more ahead pays
+    // (same box: 5 -> 137.6 us, 6 -> 134.9, 8 -> 134.5).
+    constexpr int kAhead = NT == 6 ? (PACKED ? 6 : 5) : NT;
     constexpr int kStep0 = 4 * NT; // an arbitrary stage start, for counting in absolute steps
     extern __shared__ __align__(16) char smem[];
     const lptr_t lds = (lptr_t)smem;
@@ -321,9 +329,13 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     // groups although rows are 64 bytes apart; g depends on the low four row bits only, i.e. on
     // the lane.
     const uint32_t w_g = (uint32_t)((lane >> 4) ^ (lane >> 3)) & 3u;
-    const uint64_t w_base = reinterpret_cast<uint64_t>(a.W) + (uint64_t)n0 * K2;
-    uint32_t w_lane[NEDGE ? NT : 1];
-    if constexpr (NEDGE) {
+    const uint64_t w_base = PACKED ? reinterpret_cast<uint64_t>(a.W) + ((uint64_t)(n0 >> 4) + (uint32_t)(NT * wave)) * 1024u
+                                   : reinterpret_cast<uint64_t>(a.W) + (uint64_t)n0 * K2;
+    constexpr int kWLanes = PACKED ? 1 : (NEDGE ? NT : 1);
+    uint32_t w_lane[kWLanes];
+    if constexpr (PACKED) {
+        w_lane[0] = (uint32_t)lane * 16u;
+    } else if constexpr (NEDGE) {
 #pragma unroll
         for (int i = 0; i < NT; ++i) {
             int r = WN * wave + 16 * i + (lane >> 2);
@@ -334,11 +346,14 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
     } else {
         w_lane[0] = (uint32_t)(WN * wave + (lane >> 2)) * K2 + (((uint32_t)lane & 3u) ^ w_g) * 16u;
     }
+    const uint64_t w_stage_bytes = (uint64_t)(uint32_t)a.wtiles * 1024u; // packed: bytes per stage of 32 k
     // stage at byte offset kbyte of the rows -> W buffer `buf`
     auto w_fetch = [&](int i, uint32_t kbyte, int buf) {
         const lptr_t dst = lds + kWs0 + (uint32_t)buf * kWBuf + (uint32_t)(NT * wave + i) * 1024u;
         gcptr_t src;
-        if constexpr (NEDGE)
+        if constexpr (PACKED)
+            src = (gcptr_t)(w_base + (uint64_t)(kbyte >> 6) * w_stage_bytes + (uint32_t)i * 1024u) + w_lane[0];
+        else if constexpr (NEDGE)
             src = (gcptr_t)(w_base + kbyte) + w_lane[i];
         else
             src = (gcptr_t)(w_base + kbyte + (uint64_t)i * 16u * K2) + w_lane[0];
@@ -477,13 +492,9 @@ __global__ __launch_bounds__(64 * NW, 1) void grkan_linear_fwd_kernel(const LinA
             keep_in_loop(x_lane[(1 - Q) * PPS + u]);
             xq[(1 - Q) * PPS + u] = gload16(x_base + kbyte_refill, x_lane[(1 - Q) * PPS + u]);
         }
-        if constexpr (NEDGE) {
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
-                keep_in_loop(w_lane[i]);
-        } else {
-            keep_in_loop(w_lane[0]);
-        }
+        for (int i = 0; i < kWLanes; ++i)
+            keep_in_loop(w_lane[i]);
         u32x4 y[PPS];
         fence_schedule();
         static_for<0, NT>([&](auto ntc) {
@@ -658,14 +669,15 @@ static Variant pick_variant(int32_t D_out)
     return Variant{4, 3};
 }
 
-template <typename OUT> static LinKernel select_kernel(Variant v, bool nedge)
+template <typename OUT, bool PACKED> static LinKernel select_kernel(Variant v, bool nedge)
 {
     if (v.nw == 8 && v.nt == 6)
-        return grkan_linear_fwd_kernel<8, 6, OUT, false, 5, 4>;
+        return grkan_linear_fwd_kernel<8, 6, OUT, false, PACKED, 5, 4>;
     if (v.nw == 8 && v.nt == 3)
-        return grkan_linear_fwd_kernel<8, 3, OUT, false, 5, 4>;
+        return grkan_linear_fwd_kernel<8, 3, OUT, false, PACKED, 5, 4>;
     if (v.nw == 4 && v.nt == 3)
-        return nedge ? grkan_linear_fwd_kernel<4, 3, OUT, true, 5, 4> : grkan_linear_fwd_kernel<4, 3, OUT, false, 5, 4>;
+        return nedge ? grkan_linear_fwd_kernel<4, 3, OUT, true, PACKED, 5, 4>
+                     : grkan_linear_fwd_kernel<4, 3, OUT, false, PACKED, 5, 4>;
     return nullptr;
 }
 
@@ -694,30 +706,39 @@ static bool allow_lds(const void *kernel, size_t bytes)
     return false;
 }
 
-} // namespace lin
-} // namespace grkan
-
-using namespace grkan::lin;
-
-extern "C" grkan_status_t grkan_linear_fwd(const void *x, const float *A, const float *B, const void *W,
-                                           const float *bias, void *out,
-                                           int64_t rows, int32_t D_in, int32_t D_out, int32_t G,
-                                           int32_t m, int32_t n, grkan_dtype_t io, grkan_dtype_t out_dtype,
-                                           void *hip_stream)
+// The packed copy of the weights: for stage s (32 k), 16-row tile t and lane l, the 16 bytes lane l of
+// a weight fetch brings - row 16 t + l / 4, piece (l % 4) xor g(l) of that row's 64 bytes of stage
+// s - at ((s T + t) 64 + l) 16, T tiles per stage.  Rows past D_out are zeros.
+__global__ __launch_bounds__(256) void grkan_linear_pack_w_kernel(const char *__restrict__ W, char *__restrict__ Wp,
+                                                                    int32_t K, int32_t Nout, int32_t wtiles,
+                                                                    int64_t pieces)
 {
-    if (io != GRKAN_BF16 || (out_dtype != GRKAN_BF16 && out_dtype != GRKAN_F32))
-        return GRKAN_ERR_DTYPE;
-    if (m != 5 || n != 4)
-        return GRKAN_ERR_DEGREE;
+    const uint32_t K2 = (uint32_t)K * 2u;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < pieces; idx += (int64_t)gridDim.x * 256) {
+        const uint32_t l = (uint32_t)(idx & 63);
+        const int64_t st = idx >> 6;
+        const int64_t stage = st / wtiles;
+        const int32_t t = (int32_t)(st - stage * wtiles);
+        const int32_t r = 16 * t + (int32_t)(l >> 2);
+        const uint32_t g = ((l >> 4) ^ (l >> 3)) & 3u;
+        u32x4 v = u32x4{0u, 0u, 0u, 0u};
+        if (r < Nout)
+            v = *(const u32x4 *)(W + (int64_t)r * K2 + stage * 64 + (int64_t)(((l & 3u) ^ g) * 16u));
+        *(u32x4 *)(Wp + idx * 16) = v;
+    }
+}
+
+// tiles per stage of the packed copy: whole channel blocks of the tile variant the layer runs with
+static int64_t packed_tiles(int32_t D_out)
+{
+    const int bn = pick_variant(D_out).bn();
+    return ((int64_t)D_out + bn - 1) / bn * (bn / 16);
+}
+
+static grkan_status_t linear_shape_status(int64_t rows, int32_t D_in, int32_t D_out, int32_t G)
+{
     if (rows < 0 || D_in <= 0 || D_out <= 0 || G <= 0 || D_in % G != 0)
         return GRKAN_ERR_SHAPE;
-    if (!A || !B || !W || (rows > 0 && (!x || !out)))
-        return GRKAN_ERR_NULL;
-    // 128-bit loads of x and W rows, 64/128-bit stores of four output channels, vector load of the bias
-    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(out) |
-         reinterpret_cast<uintptr_t>(bias)) % 16 != 0 ||
-        (reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 4 != 0)
-        return GRKAN_ERR_ALIGN;
     const int32_t dg = D_in / G;
     // the contraction runs in pairs of 32-k stages with one coefficient group per stage and wave;
     // a lane stores four consecutive channels
@@ -726,13 +747,41 @@ extern "C" grkan_status_t grkan_linear_fwd(const void *x, const float *A, const 
     // 32-bit lane offsets inside a tile: up to 128 rows of x and up to 768 rows of W, D_in * 2 bytes apart
     if (rows > (INT64_MAX / 8) / (D_in > D_out ? D_in : D_out) || (int64_t)D_in * 2 * 768 >= ((int64_t)1 << 32))
         return GRKAN_ERR_UNSUPPORTED;
+    return GRKAN_OK;
+}
+
+static grkan_status_t linear_fwd_impl(const void *x, const float *A, const float *B, const void *W, bool packed,
+                                      const float *bias, void *out, int64_t rows, int32_t D_in, int32_t D_out,
+                                      int32_t G, int32_t m, int32_t n, grkan_dtype_t io, grkan_dtype_t out_dtype,
+                                      void *hip_stream)
+{
+    if (io != GRKAN_BF16 || (out_dtype != GRKAN_BF16 && out_dtype != GRKAN_F32))
+        return GRKAN_ERR_DTYPE;
+    if (m != 5 || n != 4)
+        return GRKAN_ERR_DEGREE;
+    const grkan_status_t shape = linear_shape_status(rows, D_in, D_out, G);
+    if (shape != GRKAN_OK && shape != GRKAN_ERR_UNSUPPORTED)
+        return shape;
+    if (!A || !B || !W || (rows > 0 && (!x || !out)))
+        return GRKAN_ERR_NULL;
+    // 128-bit loads of x and W rows, 64/128-bit stores of four output channels, vector load of the bias
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(out) |
+         reinterpret_cast<uintptr_t>(bias)) % 16 != 0 ||
+        (reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 4 != 0)
+        return GRKAN_ERR_ALIGN;
+    if (shape != GRKAN_OK)
+        return shape;
     if (rows == 0)
         return GRKAN_OK;
 
     const Variant v = pick_variant(D_out);
     const int bn = v.bn();
     const bool nedge = D_out % bn != 0;
-    const LinKernel kernel = out_dtype == GRKAN_BF16 ? select_kernel<bf16_out>(v, nedge) : select_kernel<float>(v, nedge);
+    LinKernel kernel;
+    if (packed)
+        kernel = out_dtype == GRKAN_BF16 ? select_kernel<bf16_out, true>(v, nedge) : select_kernel<float, true>(v, nedge);
+    else
+        kernel = out_dtype == GRKAN_BF16 ? select_kernel<bf16_out, false>(v, nedge) : select_kernel<float, false>(v, nedge);
     if (!kernel)
         return GRKAN_ERR_LAUNCH;
     const size_t lds = lds_bytes(v);
@@ -749,7 +798,7 @@ extern "C" grkan_status_t grkan_linear_fwd(const void *x, const float *A, const 
     a.rows = rows;
     a.K = D_in;
     a.Nout = D_out;
-    a.dgc = dg;
+    a.dgc = D_in / G;
     const int64_t mblocks = (rows + kBM - 1) / kBM;
     const int64_t nblocks = (D_out + bn - 1) / bn;
     const int64_t grid = ((mblocks + 7) / 8) * 8 * nblocks;
@@ -757,8 +806,63 @@ extern "C" grkan_status_t grkan_linear_fwd(const void *x, const float *A, const 
         return GRKAN_ERR_UNSUPPORTED;
     a.mblocks = (int32_t)mblocks;
     a.nblocks = (int32_t)nblocks;
+    a.wtiles = (int32_t)packed_tiles(D_out);
     void *args[] = {&a};
     const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)grid), dim3(64 * v.nw),
                                          args, lds, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
+}
+
+} // namespace lin
+} // namespace grkan
+
+using namespace grkan::lin;
+
+extern "C" grkan_status_t grkan_linear_fwd(const void *x, const float *A, const float *B, const void *W,
+                                           const float *bias, void *out,
+                                           int64_t rows, int32_t D_in, int32_t D_out, int32_t G,
+                                           int32_t m, int32_t n, grkan_dtype_t io, grkan_dtype_t out_dtype,
+                                           void *hip_stream)
+{
+    return linear_fwd_impl(x, A, B, W, false, bias, out, rows, D_in, D_out, G, m, n, io, out_dtype, hip_stream);
+}
+
+extern "C" grkan_status_t grkan_linear_fwd_packed(const void *x, const float *A, const float *B, const void *Wp,
+                                                  const float *bias, void *out,
+                                                  int64_t rows, int32_t D_in, int32_t D_out, int32_t G,
+                                                  int32_t m, int32_t n, grkan_dtype_t io, grkan_dtype_t out_dtype,
+                                                  void *hip_stream)
+{
+    return linear_fwd_impl(x, A, B, Wp, true, bias, out, rows, D_in, D_out, G, m, n, io, out_dtype, hip_stream);
+}
+
+extern "C" size_t grkan_linear_packed_w_bytes(int32_t D_in, int32_t D_out)
+{
+    if (D_in <= 0 || D_out <= 0 || D_in % 64 != 0 || D_out % 4 != 0 || (int64_t)D_in * 2 * 768 >= ((int64_t)1 << 32))
+        return 0;
+    return (size_t)(D_in / 32) * (size_t)packed_tiles(D_out) * 1024u;
+}
+
+extern "C" grkan_status_t grkan_linear_pack_w(const void *W, void *Wp, int32_t D_in, int32_t D_out, void *hip_stream)
+{
+    if (D_in <= 0 || D_out <= 0)
+        return GRKAN_ERR_SHAPE;
+    const size_t bytes = grkan_linear_packed_w_bytes(D_in, D_out);
+    if (bytes == 0)
+        return GRKAN_ERR_UNSUPPORTED;
+    if (!W || !Wp)
+        return GRKAN_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(Wp)) % 16 != 0)
+        return GRKAN_ERR_ALIGN;
+    const int64_t pieces = (int64_t)(bytes / 16);
+    const int64_t want = (pieces + 255) / 256;
+    const unsigned grid = (unsigned)(want < 8192 ? want : 8192);
+    const char *w_arg = static_cast<const char *>(W);
+    char *wp_arg = static_cast<char *>(Wp);
+    int32_t tiles = (int32_t)packed_tiles(D_out);
+    int64_t n_pieces = pieces;
+    void *args[] = {&w_arg, &wp_arg, &D_in, &D_out, &tiles, &n_pieces};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(grkan_linear_pack_w_kernel), dim3(grid), dim3(256),
+                                         args, 0, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? GRKAN_OK : GRKAN_ERR_LAUNCH;
 }

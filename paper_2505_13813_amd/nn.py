@@ -210,6 +210,8 @@ class GRKANLinear(nn.Module):
         if fused not in ("inference", "always", "never"):
             raise ValueError("fused must be 'inference', 'always' or 'never'")
         self.fused = fused
+        self._packed = None      # inference: packed copy of the weights and float32 bias, remade when they change
+        self._packed_key = None
         self.rational = GroupRational(groups, init, shared_numerator, degrees)
         self.linear = nn.Linear(in_features, out_features, bias=bias)
         alpha = 1.0 / self.rational.second_moment()  # Var[x] / E[F(x)^2] with Var[x] = 1
@@ -218,13 +220,28 @@ class GRKANLinear(nn.Module):
             if bias:
                 self.linear.bias.zero_()
 
+    def _inference_weights(self):
+        """Packed weights (the kernel then fetches them in whole cache lines) and the bias in float32,
+        cached until the parameters are written to or replaced."""
+        w, b = self.linear.weight, self.linear.bias
+        key = (w.data_ptr(), w._version, w.device, None if b is None else (b.data_ptr(), b._version))
+        if self._packed_key != key:
+            self._packed = (binding.grkan_linear_pack_w(w.detach().contiguous()),
+                            None if b is None else b.detach().to(torch.float32).contiguous())
+            self._packed_key = key
+        return self._packed
+
     def forward(self, x):
         if self.fused != "never":
             A, B = self.rational.coefficient_rows()
-            want = self.fused == "always" or not torch.is_grad_enabled()
-            if want and fused_layer_supported(x, A, self.linear.weight):
-                return GRKANLayerFunction.apply(x, A.to(torch.float32), B.to(torch.float32), self.linear.weight,
-                                                self.linear.bias)
+            if fused_layer_supported(x, A, self.linear.weight):
+                if not torch.is_grad_enabled():
+                    pw, b32 = self._inference_weights()
+                    return binding.grkan_linear_fwd(x.contiguous(), A.to(torch.float32).contiguous(),
+                                                    B.to(torch.float32).contiguous(), pw, b32, out_dtype=x.dtype)
+                if self.fused == "always":
+                    return GRKANLayerFunction.apply(x, A.to(torch.float32), B.to(torch.float32), self.linear.weight,
+                                                    self.linear.bias)
         return self.linear(self.rational(x))
 
 

@@ -24,7 +24,8 @@ def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for n in ("grkan_fwd", "grkan_bwd", "grkan_bwd_workspace_bytes", "grkan_plan",
               "grkan_plan_cover_errors", "grkan_status_string", "grkan_alg1_bwd", "grkan_bwd_noalloc",
-              "grkan_tuning_override"):
+              "grkan_tuning_override", "grkan_linear_fwd", "grkan_linear_fwd_packed", "grkan_linear_pack_w",
+              "grkan_linear_packed_w_bytes"):
         assert n in names
 
 
@@ -135,3 +136,17 @@ def test_headers_are_plain_c(tmp_path):
 def test_device_query_rejects_a_null_pointer():
     lib = grkan.load_library()
     assert lib.grkan_device_query(None) == 1
+
+
+def test_packed_weight_size_is_host_arithmetic():
+    """grkan_linear_packed_w_bytes needs no GPU: (D_in / 32) stages x 16-row tiles of whole channel blocks x 1 KB."""
+    lib = binding.load_library()
+    f = lib.grkan_linear_packed_w_bytes
+    assert f(3072, 768) == (3072 // 32) * (768 // 16) * 1024 == 2 * 768 * 3072     # nothing padded
+    assert f(768, 3072) == 2 * 768 * 3072
+    assert f(1536, 384) == 2 * 1536 * 384
+    assert f(256, 200) == (256 // 32) * (384 // 16) * 1024                            # 200 -> two blocks of 192
+    assert f(64, 4) == (64 // 32) * (192 // 16) * 1024
+    assert f(100, 768) == 0 and f(3072, 770) == 0 and f(0, 768) == 0 and f(3072, -4) == 0
+    assert lib.grkan_linear_pack_w(None, None, 3072, 768, None) == 1                  # null pointers
+    assert lib.grkan_linear_pack_w(None, None, 100, 768, None) == 8                   # shape not covered

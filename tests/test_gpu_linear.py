@@ -227,3 +227,68 @@ def test_fused_layer_full_size(oracle, config, tensor, out_dtype):
     threads = max(1, min(16, oracle.max_threads()))
     check(oracle, case, out_dtype, "%s %s [%d,%d] -> %d" % (config, tensor, case["rows"], case["D_in"], case["D_out"]),
           threads=threads, full=True)
+
+
+def _packed_layout_numpy(W_bits, D_out, D_in, bn):
+    """The packed copy as include/grkan.h describes it, from the bfloat16 bit patterns (data movement only)."""
+    T = -(-D_out // bn) * (bn // 16)
+    stages = D_in // 32
+    Wp = np.zeros((stages, T, 64, 8), np.uint16)
+    rows_pad = np.zeros((T * 16, D_in), np.uint16)
+    rows_pad[:D_out] = W_bits.view(np.uint16).reshape(D_out, D_in)
+    lanes = np.arange(64)
+    g = ((lanes >> 4) ^ (lanes >> 3)) & 3
+    piece = (lanes & 3) ^ g
+    for s in range(stages):
+        blk = rows_pad[:, 32 * s:32 * s + 32].reshape(T, 16, 4, 8)          # [tile, row in tile, piece, 8 values]
+        Wp[s] = blk[:, lanes >> 2, piece, :]
+    return Wp.reshape(-1)
+
+
+@pytest.mark.parametrize("D_in,D_out,bn", [(256, 768, 768), (128, 384, 384), (64, 200, 192), (192, 1152, 384)])
+def test_packed_weights_have_the_documented_layout(D_in, D_out, bn):
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    rng = np.random.default_rng(D_in + D_out)
+    W_bits = grkan_inputs.round_to_bf16_bits(rng.standard_normal((D_out, D_in)).astype(np.float32))
+    W = torch.from_numpy(np.ascontiguousarray(W_bits).view(np.int16)).to("cuda:0").view(torch.bfloat16)
+    pw = grkan.grkan_linear_pack_w(W)
+    torch.cuda.synchronize()
+    got = pw.data.cpu().numpy().view(np.uint16)
+    want = _packed_layout_numpy(W_bits, D_out, D_in, bn)
+    assert got.shape == want.shape and np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("rows,D_in,D_out,G", SHAPES + _random_shapes(6, 77))
+def test_packed_weights_give_bit_identical_outputs(rows, D_in, D_out, G):
+    # same arithmetic and summation order, only the weights' addresses differ
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    case = custom_linear_case(rows + D_in + D_out + G, rows, D_in, D_out, G, bias=True)
+    dev = grkan_inputs.upload_linear(case)
+    pw = grkan.grkan_linear_pack_w(dev["W"])
+    for dt in (torch.bfloat16, torch.float32):
+        a = grkan.grkan_linear_fwd(dev["x"], dev["A"], dev["B"], dev["W"], dev["bias"], out_dtype=dt)
+        b = grkan.grkan_linear_fwd(dev["x"], dev["A"], dev["B"], pw, dev["bias"], out_dtype=dt)
+        torch.cuda.synchronize()
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (rows, D_in, D_out, G, dt)
+
+
+def test_packed_weights_full_size_bit_identical():
+    import torch
+
+    import paper_2505_13813_amd as grkan
+
+    case = grkan_inputs.make_linear_case("kat_b", "x2")
+    dev = grkan_inputs.upload_linear(case)
+    pw = grkan.grkan_linear_pack_w(dev["W"])
+    a = grkan.grkan_linear_fwd(dev["x"], dev["A"], dev["B"], dev["W"], dev["bias"])
+    b = grkan.grkan_linear_fwd(dev["x"], dev["A"], dev["B"], pw, dev["bias"])
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    with pytest.raises(ValueError):
+        grkan.grkan_linear_fwd(dev["x"][:, :1536].contiguous(), dev["A"], dev["B"], pw)   # made for another D_in

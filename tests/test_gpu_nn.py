@@ -147,3 +147,13 @@ def test_fused_layer_module_forward_and_backward(oracle):
     auto.load_state_dict(layer.state_dict())
     with torch.no_grad():
         assert torch.equal(auto(x).view(torch.int16), direct.view(torch.int16))
+        # the packed copy of the weights is remade when the weights are written to
+        first = auto._packed[0]
+        assert auto(x) is not None and auto._packed[0] is first
+        auto.linear.weight.mul_(0.5)
+        auto.linear.bias.add_(1.0)
+        again = auto(x)
+        assert auto._packed[0] is not first
+        want = grkan.grkan_linear_fwd(x.detach(), A.float().contiguous(), B.float().contiguous(),
+                                      auto.linear.weight.detach(), auto.linear.bias.detach().float())
+        assert torch.equal(again.view(torch.int16), want.view(torch.int16))
