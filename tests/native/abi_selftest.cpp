@@ -247,6 +247,34 @@ static bool run_linear_case(const LinCase &c, uint64_t seed)
     HIP_OK(hipStreamSynchronize(stream));
     std::vector<float> out(MO);
     HIP_OK(hipMemcpy(out.data(), d_out, MO * 4, hipMemcpyDeviceToHost));
+    {
+        // the same layer from the packed copy of the weights: bit-identical
+        const size_t pbytes = grkan_linear_packed_w_bytes(c.D_in, c.D_out);
+        void *d_Wp, *d_out2;
+        if (pbytes == 0) {
+            std::printf("FAIL grkan_linear_packed_w_bytes returned 0\n");
+            return false;
+        }
+        HIP_OK(hipMalloc(&d_Wp, pbytes));
+        HIP_OK(hipMalloc(&d_out2, MO * 4));
+        grkan_status_t sp = grkan_linear_pack_w(d_W, d_Wp, c.D_in, c.D_out, stream);
+        if (sp == GRKAN_OK)
+            sp = grkan_linear_fwd_packed(d_x, d_A, d_B, d_Wp, d_bias, d_out2, c.rows, c.D_in, c.D_out, c.G, m, n,
+                                         GRKAN_BF16, GRKAN_F32, stream);
+        if (sp != GRKAN_OK) {
+            std::printf("packed path failed: %s\n", grkan_status_string(sp));
+            return false;
+        }
+        HIP_OK(hipStreamSynchronize(stream));
+        std::vector<float> out2(MO);
+        HIP_OK(hipMemcpy(out2.data(), d_out2, MO * 4, hipMemcpyDeviceToHost));
+        HIP_OK(hipFree(d_Wp));
+        HIP_OK(hipFree(d_out2));
+        if (std::memcmp(out.data(), out2.data(), MO * 4)) {
+            std::printf("FAIL grkan_linear_fwd_packed differs from grkan_linear_fwd\n");
+            return false;
+        }
+    }
     HIP_OK(hipStreamDestroy(stream));
     for (void *p : {d_x, d_W, d_out, (void *)d_A, (void *)d_B, (void *)d_bias})
         HIP_OK(hipFree(p));
