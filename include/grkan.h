@@ -201,6 +201,11 @@ grkan_status_t grkan_bwd(const void *x, const void *dy, const float *A, const fl
  * workspace, results independent of the launch (fixed summation order per
  * output).  The first call of a kernel variant on a device raises that kernel's
  * dynamic-LDS limit (no allocation).
+ * Sizing: a workgroup owns 112 rows x one channel block (768, 384 or 192
+ * channels) and walks the whole of D_in by itself, so the kernel is at its best
+ * from about as many such tiles as the chip has compute units (at 3072 -> 768:
+ * from about 20,000 rows); far below that, grkan_fwd and a library product are
+ * the faster route.
  */
 grkan_status_t grkan_linear_fwd(const void *x, const float *A, const float *B, const void *W,
                                 const float *bias, void *out,

@@ -80,6 +80,18 @@ def fused_layer_supported(x, A, weight) -> bool:
             and D_in % 64 == 0 and D_in % G == 0 and (D_in // G) % 32 == 0 and int(weight.shape[0]) % 4 == 0)
 
 
+def fused_layer_pays(rows: int, D_in: int, D_out: int) -> bool:
+    """Whether the one-kernel layer is the faster route at this size (measured on MI355X, bfloat16).
+    A workgroup owns 112 tokens x one channel block (768, 384 or 192 channels) and walks the whole
+    contraction by itself, so the kernel needs about as many workgroups as the chip has compute units:
+    at D_in = 3072 -> 768 it takes 109 us for anything up to 6,000 tokens (the two kernels: 34 - 53 us)
+    and wins from about 20,000 tokens on (135 against 192 us at 25,216); with a short contraction
+    (D_in <= 768) a workgroup is quick and one launch instead of two wins at every size measured."""
+    bn = 768 if D_out % 768 == 0 else (384 if D_out % 384 == 0 else 192)
+    workgroups = -(-int(rows) // 112) * -(-int(D_out) // bn)
+    return workgroups >= 200 or D_in <= 768
+
+
 class GRKANLayerFunction(torch.autograd.Function):
     """out = F(x) W^T + bias with the forward pass in one kernel (F never written to memory) and
     nothing but x, A, B, W saved.  The backward pass recomputes F(x) for dW = dOut^T F(x)
@@ -202,8 +214,9 @@ class GRKANLinear(nn.Module):
                  bias: bool = True, shared_numerator: bool = True,
                  degrees: Tuple[int, int] = (M_DEGREE, N_DEGREE), fused: str = "inference"):
         """`fused`: when the one-kernel layer (F inside the matrix product) is used where it applies
-        (bfloat16, see fused_layer_supported): "inference" = only when no gradient is recorded (the
-        default: in training its backward pass has to recompute F(x)), "always", or "never"."""
+        (bfloat16, see fused_layer_supported): "inference" = when no gradient is recorded (in training
+        its backward pass has to recompute F(x)) and the input is large enough for it to be the faster
+        route (fused_layer_pays); "always" = wherever it applies; "never"."""
         super().__init__()
         if in_features % groups:
             raise ValueError("in_features must be a multiple of groups")
@@ -235,7 +248,9 @@ class GRKANLinear(nn.Module):
         if self.fused != "never":
             A, B = self.rational.coefficient_rows()
             if fused_layer_supported(x, A, self.linear.weight):
-                if not torch.is_grad_enabled():
+                rows = x.numel() // x.shape[-1]
+                pays = self.fused == "always" or fused_layer_pays(rows, x.shape[-1], self.linear.weight.shape[0])
+                if not torch.is_grad_enabled() and pays:
                     pw, b32 = self._inference_weights()
                     return binding.grkan_linear_fwd(x.contiguous(), A.to(torch.float32).contiguous(),
                                                     B.to(torch.float32).contiguous(), pw, b32, out_dtype=x.dtype)

@@ -74,3 +74,16 @@ def test_cpu_tensors_are_refused():
         layer(torch.zeros(4, 192))
     with pytest.raises(ValueError):
         gnn.GRKANLinear(100, 10, groups=8)
+
+
+def test_fused_layer_size_rule():
+    """The module takes the one-kernel layer only where it fills the chip (or the contraction is short)."""
+    from paper_2505_13813_amd.nn import fused_layer_pays
+
+    assert fused_layer_pays(25216, 3072, 768)          # KAT-B second layer at batch 128: 226 workgroups
+    assert not fused_layer_pays(12608, 3072, 768)      # half the batch: 113 workgroups, the two kernels are faster
+    assert not fused_layer_pays(197, 3072, 768)        # one image
+    assert fused_layer_pays(25216, 1536, 384)          # KAT-S second layer
+    assert not fused_layer_pays(6304, 1536, 384)
+    assert fused_layer_pays(197, 768, 192)             # short contraction: one launch instead of two
+    assert fused_layer_pays(6000, 3072, 3072)          # many channel blocks make up for few tokens
