@@ -234,13 +234,16 @@ class GRKANLinear(nn.Module):
                 self.linear.bias.zero_()
 
     def _inference_weights(self):
-        """Packed weights (the kernel then fetches them in whole cache lines) and the bias in float32,
-        cached until the parameters are written to or replaced."""
-        w, b = self.linear.weight, self.linear.bias
-        key = (w.data_ptr(), w._version, w.device, None if b is None else (b.data_ptr(), b._version))
+        """Packed weights (the kernel then fetches them in whole cache lines), the bias and the
+        coefficient rows in float32, cached until a parameter is written to or replaced."""
+        params = (self.linear.weight, self.linear.bias, self.rational.numerator, self.rational.denominator)
+        key = tuple(None if p is None else (p.data_ptr(), p._version, p.device) for p in params)
         if self._packed_key != key:
+            w, b = self.linear.weight, self.linear.bias
+            A, B = self.rational.coefficient_rows()
             self._packed = (binding.grkan_linear_pack_w(w.detach().contiguous()),
-                            None if b is None else b.detach().to(torch.float32).contiguous())
+                            None if b is None else b.detach().to(torch.float32).contiguous(),
+                            A.detach().to(torch.float32).contiguous(), B.detach().to(torch.float32).contiguous())
             self._packed_key = key
         return self._packed
 
@@ -251,9 +254,8 @@ class GRKANLinear(nn.Module):
                 rows = x.numel() // x.shape[-1]
                 pays = self.fused == "always" or fused_layer_pays(rows, x.shape[-1], self.linear.weight.shape[0])
                 if not torch.is_grad_enabled() and pays:
-                    pw, b32 = self._inference_weights()
-                    return binding.grkan_linear_fwd(x.contiguous(), A.to(torch.float32).contiguous(),
-                                                    B.to(torch.float32).contiguous(), pw, b32, out_dtype=x.dtype)
+                    pw, b32, A32, B32 = self._inference_weights()
+                    return binding.grkan_linear_fwd(x.contiguous(), A32, B32, pw, b32, out_dtype=x.dtype)
                 if self.fused == "always":
                     return GRKANLayerFunction.apply(x, A.to(torch.float32), B.to(torch.float32), self.linear.weight,
                                                     self.linear.bias)

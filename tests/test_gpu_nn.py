@@ -157,3 +157,9 @@ def test_fused_layer_module_forward_and_backward(oracle):
         want = grkan.grkan_linear_fwd(x.detach(), A.float().contiguous(), B.float().contiguous(),
                                       auto.linear.weight.detach(), auto.linear.bias.detach().float())
         assert torch.equal(again.view(torch.int16), want.view(torch.int16))
+        # ... and when the rational function's coefficients are
+        auto.rational.denominator.add_(0.01)
+        A2, B2 = auto.rational.coefficient_rows()
+        want = grkan.grkan_linear_fwd(x.detach(), A2.float().contiguous(), B2.float().contiguous(),
+                                      auto.linear.weight.detach(), auto.linear.bias.detach().float())
+        assert torch.equal(auto(x).view(torch.int16), want.view(torch.int16))
